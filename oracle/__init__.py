@@ -1,0 +1,262 @@
+"""CPU oracle of the decode step -- TEST INFRASTRUCTURE, not product code.
+
+``decode_oracle.c`` states what the step computes; this file only compiles it with gcc, loads
+it with ctypes and marshals numpy arrays into it.  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the HIP path never does.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "decode_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+# plain IEEE arithmetic: no fast-math, no fused multiply-add contraction
+_CFLAGS = ["-O2", "-ftree-vectorize", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11"]
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc.  AVX2 is used when this CPU has it (it only widens the
+    loops that run over independent outputs; every sum keeps its ascending order)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    flags = list(_CFLAGS)
+    try:
+        with open("/proc/cpuinfo") as f:
+            if " avx2 " in f.read():
+                flags.append("-mavx2")
+    except OSError:
+        pass
+    tmp = _LIB + ".tmp.%d" % os.getpid()
+    subprocess.run(["gcc", *flags, _SRC, "-o", tmp, "-lm"], check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
+                                         "intermediate", "vocab", "block_size", "qkv_bias", "round_act")]
+    _fields_ += [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "bqkv", "wo", "g2", "wg", "wu", "wd")]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("gf", C.c_void_p), ("wlm", C.c_void_p), ("layers", C.POINTER(_Layer))]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared object (built on first use when absent or older than its source)."""
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        L.orc_bf16_to_f32.restype = C.c_float
+        L.orc_bf16_to_f32.argtypes = [C.c_uint16]
+        L.orc_f32_to_bf16.restype = C.c_uint16
+        L.orc_f32_to_bf16.argtypes = [C.c_float]
+        L.orc_silu.restype = C.c_float
+        L.orc_silu.argtypes = [C.c_float]
+        L.orc_argmax.restype = C.c_int32
+        L.orc_head.restype = C.c_int32
+        L.orc_decode_step.restype = C.c_int
+        L.orc_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _u16(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def make_config(shape, round_act: bool = True, block_size: Optional[int] = None) -> _Config:
+    """orc_config from any object with the ModelShape field names."""
+    return _Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                   shape.intermediate, shape.vocab, block_size or shape.block_size,
+                   1 if shape.qkv_bias else 0, 1 if round_act else 0, shape.rms_eps, shape.rope_theta)
+
+
+# ---- elementary operations (used by the pins) ------------------------------------------------
+
+def bf16_round_bits(x) -> np.ndarray:
+    """uint16 bf16 patterns of fp32 values, through the oracle's own rounding."""
+    x = _f32(x)
+    out = np.empty(x.shape, dtype=np.uint16)
+    f = lib().orc_f32_to_bf16
+    flat, o = x.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = f(float(flat[i]))
+    return out
+
+
+def rmsnorm(x, g_bits, eps: float) -> np.ndarray:
+    x = _f32(x)
+    y = np.empty_like(x)
+    lib().orc_rmsnorm(_p(x), _p(_u16(g_bits)), C.c_int(x.size), C.c_float(eps), _p(y))
+    return y
+
+
+def linear(x, w_bits, bias_bits=None) -> np.ndarray:
+    x = _f32(x)
+    w_bits = _u16(w_bits)
+    K, N = w_bits.shape
+    assert x.shape == (K,)
+    y = np.empty(N, dtype=np.float32)
+    lib().orc_linear(_p(x), _p(w_bits), _p(None if bias_bits is None else _u16(bias_bits)),
+                     C.c_int(K), C.c_int(N), _p(y))
+    return y
+
+
+def rope(v, pos: int, theta: float) -> np.ndarray:
+    v = _f32(v).copy()
+    lib().orc_rope(_p(v), C.c_int(v.size), C.c_int(pos), C.c_float(theta))
+    return v
+
+
+def softmax(s) -> np.ndarray:
+    s = _f32(s)
+    p = np.empty_like(s)
+    lib().orc_softmax(_p(s), C.c_int(s.size), _p(p))
+    return p
+
+
+def silu(x: float) -> float:
+    return float(lib().orc_silu(C.c_float(x)))
+
+
+def argmax(x) -> int:
+    x = _f32(x)
+    return int(lib().orc_argmax(_p(x), C.c_int(x.size)))
+
+
+# ---- model-level objects -----------------------------------------------------------------------
+
+class Weights:
+    """Host bf16 bit patterns (uint16 numpy arrays) of a whole model, in the oracle's structs."""
+
+    def __init__(self, global_w: Dict[str, np.ndarray], layers: Sequence[Dict[str, np.ndarray]]):
+        self._keep: List[np.ndarray] = []
+        arr = (_Layer * len(layers))()
+        for i, lw in enumerate(layers):
+            for name in ("g1", "wqkv", "bqkv", "wo", "g2", "wg", "wu", "wd"):
+                a = _u16(lw[name])
+                self._keep.append(a)
+                setattr(arr[i], name, a.ctypes.data)
+        self._layers = arr
+        g = {k: _u16(global_w[k]) for k in ("embed", "gf", "wlm")}
+        self._keep.extend(g.values())
+        self.struct = _Weights(g["embed"].ctypes.data, g["gf"].ctypes.data, g["wlm"].ctypes.data, arr)
+        self.n_layers = len(layers)
+
+    def layer(self, i: int) -> _Layer:
+        return self._layers[i]
+
+
+class PagedKV:
+    """The oracle's own paged cache: per layer, K and V pools [num_blocks, block_size, n_kv_heads,
+    head_dim] of bf16 bit patterns."""
+
+    def __init__(self, cfg: _Config, num_blocks: int, n_layers: Optional[int] = None):
+        L = cfg.n_layers if n_layers is None else n_layers
+        shp = (num_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim)
+        self.k = [np.zeros(shp, dtype=np.uint16) for _ in range(L)]
+        self.v = [np.zeros(shp, dtype=np.uint16) for _ in range(L)]
+        self.cfg = cfg
+        self.kptr = (C.c_void_p * L)(*[a.ctypes.data for a in self.k])
+        self.vptr = (C.c_void_p * L)(*[a.ctypes.data for a in self.v])
+
+    def fill(self, layer: int, k_bits, v_bits, seq_start, block_table) -> None:
+        """Scatter concatenated K/V rows [tokens, n_kv_heads, head_dim] of one layer."""
+        bt = _i32(block_table)
+        ss = _i32(seq_start)
+        lib().orc_kv_fill(C.byref(self.cfg), _p(self.k[layer]), _p(self.v[layer]), _p(_u16(k_bits)),
+                          _p(_u16(v_bits)), _p(ss), _p(bt), C.c_int(bt.shape[1]), C.c_int(ss.size - 1))
+
+
+def attention(cfg: _Config, q, kpool, vpool, table_row, T: int) -> np.ndarray:
+    """One sequence, one layer: q [n_q_heads*head_dim] fp32 -> o [n_q_heads*head_dim]."""
+    q = _f32(q).reshape(-1)
+    o = np.empty_like(q)
+    lib().orc_attention(C.byref(cfg), _p(q), _p(_u16(kpool)), _p(_u16(vpool)), _p(_i32(table_row)),
+                        C.c_int(T), _p(o))
+    return o
+
+
+def layer_step(cfg: _Config, layer: _Layer, x, pos: int, kpool, vpool, table_row,
+               want_attn: bool = False):
+    """One decoder layer for one sequence; x (fp32 [hidden]) is updated in place."""
+    assert x.dtype == np.float32 and x.flags.c_contiguous
+    attn = np.empty(cfg.n_q_heads * cfg.head_dim, dtype=np.float32) if want_attn else None
+    lib().orc_layer_step(C.byref(cfg), C.byref(layer), _p(x), C.c_int(pos), _p(kpool), _p(vpool),
+                         _p(_i32(table_row)), _p(attn))
+    return attn
+
+
+def embed(cfg: _Config, w: Weights, token: int) -> np.ndarray:
+    x = np.empty(cfg.hidden, dtype=np.float32)
+    lib().orc_embed(C.byref(cfg), C.byref(w.struct), C.c_int32(token), _p(x))
+    return x
+
+
+def head(cfg: _Config, w: Weights, x):
+    """Final norm + LM head + greedy token for one residual row."""
+    logits = np.empty(cfg.vocab, dtype=np.float32)
+    tok = lib().orc_head(C.byref(cfg), C.byref(w.struct), _p(_f32(x)), _p(logits))
+    return logits, int(tok)
+
+
+def decode_step(cfg: _Config, w: Weights, kv: PagedKV, tokens, positions, seq_lens, block_table,
+                want_attn: bool = False):
+    """One decode step for a batch.  Returns (logits [B, vocab], next_tokens [B], attn or None)
+    where attn is [n_layers, B, n_q_heads*head_dim] before its bf16 rounding."""
+    tokens, positions, seq_lens = _i32(tokens), _i32(positions), _i32(seq_lens)
+    bt = _i32(block_table)
+    B = tokens.size
+    logits = np.empty((B, cfg.vocab), dtype=np.float32)
+    nxt = np.empty(B, dtype=np.int32)
+    attn = np.empty((cfg.n_layers, B, cfg.n_q_heads * cfg.head_dim), dtype=np.float32) if want_attn else None
+    rc = lib().orc_decode_step(C.byref(cfg), C.byref(w.struct), C.c_int(B), _p(tokens), _p(positions),
+                               _p(seq_lens), _p(bt), C.c_int(bt.shape[1]), kv.kptr, kv.vptr,
+                               _p(logits), _p(nxt), _p(attn))
+    if rc != 0:
+        raise ValueError("seq_lens must equal positions + 1")
+    return logits, nxt, attn
+
+
+def full_causal(cfg: _Config, w: Weights, tokens, want_attn: bool = False):
+    """Dense causal recomputation of all positions of one sequence (no cache, no paging)."""
+    tokens = _i32(tokens)
+    n = tokens.size
+    logits = np.empty((n, cfg.vocab), dtype=np.float32)
+    attn = np.empty((cfg.n_layers, n, cfg.n_q_heads * cfg.head_dim), dtype=np.float32) if want_attn else None
+    lib().orc_full_causal(C.byref(cfg), C.byref(w.struct), _p(tokens), C.c_int(n), _p(logits), _p(attn))
+    return logits, attn
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
