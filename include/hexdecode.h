@@ -1,0 +1,206 @@
+/*
+ * hexdecode.h -- C ABI of the MI355X rollout decode-step library (libhexdecode.so).
+ *
+ * What it computes.  The paper splits asynchronous RL into rollout generation, reward and
+ * training, and characterises rollout generation as HBM-I/O-bound inference that dominates the
+ * workflow (Section 1; Section 3, Observation 1; Section 4.1, the C_I > C_T assumption; Section
+ * 5.3, Discussion); its policy models are distilled Qwen-2.5 decoders of 1.5B / 7B / 14B
+ * parameters (Section 5.2) whose response lengths are skewed (Section 4.2.2).  The paper gives no
+ * kernel-level description, so the operation is the textbook one: ONE autoregressive decode
+ * step of a Qwen2-style decoder (RMSNorm, q/k/v projection with bias, rotate-half RoPE,
+ * grouped-query attention over a paged KV cache, SwiGLU MLP, LM head, greedy argmax) for a
+ * batch of independent sequences with ragged context lengths.
+ *
+ * Numeric contract.  Weights, KV cache and every matrix-product input are bf16; all arithmetic
+ * accumulates in fp32; the residual stream stays fp32.  Activations are rounded to bf16
+ * (nearest-even) at the five matrix-product inputs, at the rotated query and at K/V cache
+ * writes, nowhere else (softmax probabilities may be rounded to bf16 inside the P*V product).
+ *
+ * Conventions for every function.
+ *   - extern "C"; returns hx_status: 0 on success, negative on error.  Never throws, never aborts.
+ *     hx_last_error() returns a static, thread-local description of the last failure.
+ *   - "DEVICE" pointers are HIP device addresses owned by the caller (e.g. torch.empty(...,
+ *     device="cuda")); the library never allocates or frees device memory and keeps only the
+ *     addresses.  "HOST" pointers are ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *     enqueued on it and the call returns without synchronising; results are valid once the
+ *     stream reaches that point.  Scalar arguments are validated on the host before anything is
+ *     enqueued; the CONTENT of device arrays (token ids, block ids, lengths) is not validated:
+ *     out-of-range content is undefined behaviour.
+ *   - One engine / kv handle may be used by one thread at a time; calls on the same engine must
+ *     be stream-ordered (they share the workspace).
+ */
+#ifndef HEXDECODE_H
+#define HEXDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hx_engine hx_engine; /* host-side handle: model shape, packed-weight map, workspace map */
+typedef struct hx_kv hx_kv;         /* host-side handle: view of a caller-owned paged KV pool           */
+
+/* Shape of the decoder and limits of the deployment.  Set struct_size = sizeof(hx_model_config). */
+typedef struct {
+    uint32_t struct_size;
+    int32_t n_layers;
+    int32_t hidden;       /* multiple of 32                                         */
+    int32_t n_q_heads;    /* multiple of n_kv_heads, at most 16 query heads per KV head */
+    int32_t n_kv_heads;
+    int32_t head_dim;     /* 64 or 128                                              */
+    int32_t intermediate; /* multiple of 16                                         */
+    int32_t vocab;
+    int32_t block_size;   /* tokens per KV block; must be 16                        */
+    int32_t qkv_bias;     /* 1: q/k/v projections carry a bias                      */
+    float rms_eps;
+    float rope_theta;
+    int32_t max_batch;    /* 1..256 sequences per decode step                        */
+    int32_t max_seq_len;  /* largest KV length (new token included) of any sequence  */
+} hx_model_config;
+
+typedef enum {
+    HX_OK = 0,
+    HX_E_NULL = -1,      /* a required pointer is NULL                               */
+    HX_E_CONFIG = -2,    /* unsupported or inconsistent hx_model_config              */
+    HX_E_SHAPE = -3,     /* rows/cols/batch/layer/kind do not match the configuration */
+    HX_E_ALIGN = -4,     /* a device buffer is not 256-byte aligned                  */
+    HX_E_TOO_SMALL = -5, /* a caller buffer is smaller than the size query says      */
+    HX_E_RANGE = -6,     /* a scalar argument is out of range                        */
+    HX_E_HIP = -7        /* the HIP runtime reported an error (text in hx_last_error) */
+} hx_status;
+
+/* Logical tensors of the model, all bf16 row-major [in, out] (vectors: [n]). */
+typedef enum {
+    HX_T_EMBED = 0, /* [vocab, hidden]  (layer ignored)            */
+    HX_T_G1 = 1,    /* [hidden]  gain of the attention-block norm   */
+    HX_T_WQKV = 2,  /* [hidden, (n_q_heads + 2 n_kv_heads) head_dim], columns q | k | v */
+    HX_T_BQKV = 3,  /* [(n_q_heads + 2 n_kv_heads) head_dim]        */
+    HX_T_WO = 4,    /* [n_q_heads head_dim, hidden]                 */
+    HX_T_G2 = 5,    /* [hidden]  gain of the MLP-block norm         */
+    HX_T_WG = 6,    /* [hidden, intermediate]  gate projection      */
+    HX_T_WU = 7,    /* [hidden, intermediate]  up projection        */
+    HX_T_WD = 8,    /* [intermediate, hidden]  down projection      */
+    HX_T_GF = 9,    /* [hidden]  final gain      (layer ignored)    */
+    HX_T_WLM = 10   /* [hidden, vocab]  LM head  (layer ignored)    */
+} hx_tensor_kind;
+
+const char *hx_last_error(void);
+
+/* ---- sizes of the caller-provided device buffers (HOST out-pointers) -------------------------- */
+
+/* Bytes of the packed-weight buffer (all tensors above in the library's streaming layout). */
+int hx_weights_bytes(const hx_model_config *cfg, size_t *out);
+/* Bytes of the workspace: activations, split-K partial results, work list, per-step tables. */
+int hx_workspace_bytes(const hx_model_config *cfg, size_t *out);
+/* Bytes of a KV pool of `num_blocks` physical blocks (all layers, K and V). */
+int hx_kv_bytes(const hx_model_config *cfg, int64_t num_blocks, size_t *out);
+
+/* ---- engine ------------------------------------------------------------------------------------ */
+
+/* Wraps caller-owned DEVICE buffers (256-byte aligned, at least the sizes above).  No device work
+   is done.  The buffers must outlive the engine.  *out receives a handle released with
+   hx_engine_destroy (which frees host state only). */
+int hx_engine_create(const hx_model_config *cfg, void *weights_dev, size_t weights_bytes,
+                     void *workspace_dev, size_t workspace_bytes, hx_engine **out);
+int hx_engine_destroy(hx_engine *engine);
+
+/* Re-packs ONE logical tensor (DEVICE, bf16, row-major [rows, cols], contiguous) into the engine's
+   weight buffer: matrices go to the operand order of the matrix-core instructions so that a
+   wavefront streams them with contiguous 1-KiB loads; vectors and the embedding are copied.
+   HX_T_WG and HX_T_WU of a layer share one interleaved packed matrix; each may be packed
+   independently.  `src_dev` may be released once the stream has passed the call.  This is also
+   the weight-update path after a policy update (Section 2, weight synchronisation). */
+int hx_weights_pack(hx_engine *engine, int tensor_kind, int layer, const void *src_dev,
+                    int64_t rows, int64_t cols, void *stream);
+
+/* ---- paged KV cache ------------------------------------------------------------------------------ */
+
+/* Wraps a caller-owned DEVICE pool (256-byte aligned, >= hx_kv_bytes(num_blocks)) as a paged
+   cache of `num_blocks` blocks of 16 tokens.  Pool layout: [layer][block][kv_head][K tile | V tile];
+   a tile holds the 16 x head_dim bf16 values of one block and KV head in matrix-core operand
+   order, so one wavefront load instruction covers 1 KiB of contiguous memory.  The content is
+   not initialised.  *out is released with kv_free. */
+int kv_alloc(hx_engine *engine, void *kv_dev, size_t kv_bytes, int64_t num_blocks, hx_kv **out);
+int kv_free(hx_kv *kv);
+
+/* Scatters caller-supplied K and V of ONE layer into the pool.  k_dev / v_dev: DEVICE bf16
+   [total_tokens, n_kv_heads, head_dim], the sequences concatenated in batch order;
+   seq_start_dev: DEVICE int32 [batch + 1], token offset of each sequence (seq_start[batch] =
+   total_tokens); token p of sequence b goes to block block_table[b][p / 16], slot p % 16.
+   block_table_dev: DEVICE int32 [batch, max_blocks_per_seq]. */
+int prefill_fill(hx_kv *kv, int layer, const void *k_dev, const void *v_dev,
+                 const int32_t *seq_start_dev, const int32_t *block_table_dev,
+                 int32_t max_blocks_per_seq, int32_t batch, int64_t total_tokens, void *stream);
+
+/* Inverse of prefill_fill (test / checkpoint hook): gathers the cached K and V of ONE layer back
+   into logical layout k_out_dev / v_out_dev [total_tokens, n_kv_heads, head_dim] bf16. */
+int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_dev,
+                 const int32_t *seq_start_dev, const int32_t *block_table_dev,
+                 int32_t max_blocks_per_seq, int32_t batch, int64_t total_tokens, void *stream);
+
+/* ---- the decode step ------------------------------------------------------------------------------ */
+
+/* One autoregressive step for `batch` sequences.  All array arguments are DEVICE pointers.
+     tokens      int32 [batch]   id of the token to process for each sequence
+     positions   int32 [batch]   its position = number of tokens already cached
+     seq_lens    int32 [batch]   keys attended = positions + 1 (the new token attends itself)
+     block_table int32 [batch, max_blocks_per_seq]  physical block of each logical block; entries
+                                 past ceil(seq_lens/16) are ignored
+     logits_out  fp32 [batch, vocab] or NULL (then the logits are not written)
+     next_tokens_out int32 [batch]   smallest index attaining the row maximum of the logits
+   Side effect: K and V of the new token are written into `kv` at `positions` for every layer.
+   The step is deterministic: the same inputs give the same bits. */
+int decode_step(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *tokens,
+                const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
+                int32_t max_blocks_per_seq, float *logits_out, int32_t *next_tokens_out, void *stream);
+
+/* Parity hook: when attn_dev is not NULL every following decode_step also writes the attention
+   output of every layer BEFORE its bf16 rounding to attn_dev, DEVICE fp32
+   [n_layers, batch, n_q_heads * head_dim] (batch = that step's batch).  NULL switches it off. */
+int hx_set_attn_capture(hx_engine *engine, float *attn_dev);
+
+/* ---- single stages (test and measurement hooks; the same kernels decode_step launches) ------------ */
+
+/* Work list of the split-K attention: sequence b contributes ceil(seq_lens[b] / chunk) items
+   (b, c), listed in batch order; chunk = hx_attention_chunk(engine).  Outputs are DEVICE int32:
+   n_items_out [1], item_seq_out / item_chunk_out [>= batch * ceil(max_seq_len / chunk)],
+   first_item_out [batch + 1] (exclusive prefix sum of the per-sequence item counts). */
+int hx_stage_worklist(hx_engine *engine, int32_t batch, const int32_t *seq_lens, int32_t *n_items_out,
+                      int32_t *item_seq_out, int32_t *item_chunk_out, int32_t *first_item_out,
+                      void *stream);
+int hx_attention_chunk(const hx_engine *engine); /* tokens per split-K work item */
+
+/* bias + RoPE + cache append of one layer: qkv_dev fp32 [batch, qkv_cols] is the projection WITHOUT
+   bias (the packed bias of `layer` is added); writes K/V of position positions[b] into `kv` and
+   returns the rotated, bf16-rounded query as fp32 in q_out_dev [batch, n_q_heads * head_dim]. */
+int hx_stage_rope_append(hx_engine *engine, hx_kv *kv, int layer, int32_t batch, const float *qkv_dev,
+                         const int32_t *positions, const int32_t *block_table,
+                         int32_t max_blocks_per_seq, float *q_out_dev, void *stream);
+
+/* Attention of one layer over the cache as it stands: q_dev fp32 [batch, n_q_heads * head_dim]
+   (rounded to bf16 on entry), out_dev fp32 [batch, n_q_heads * head_dim] before rounding. */
+int hx_stage_attention(hx_engine *engine, hx_kv *kv, int layer, int32_t batch, const float *q_dev,
+                       const int32_t *seq_lens, const int32_t *block_table,
+                       int32_t max_blocks_per_seq, float *out_dev, void *stream);
+
+/* RMSNorm with the packed gain `gain_kind` (HX_T_G1 / HX_T_G2 / HX_T_GF): x_dev fp32
+   [batch, hidden] -> y_dev fp32 [batch, hidden] holding the bf16-rounded result. */
+int hx_stage_rmsnorm(hx_engine *engine, int gain_kind, int layer, int32_t batch, const float *x_dev,
+                     float *y_dev, void *stream);
+
+/* One weight-streaming matrix product with the packed tensor `matrix_kind`:
+     HX_T_WQKV: y [batch, qkv_cols] = R(x) W (no bias)      HX_T_WO: y [batch, hidden] = R(x) W
+     HX_T_WG  : y [batch, intermediate] = R( silu(R(x) Wg) * (R(x) Wu) ) as fp32
+     HX_T_WD  : y [batch, hidden] = R(x) W                   HX_T_WLM: y [batch, vocab] = R(x) W
+   x_dev fp32 [batch, in] is rounded to bf16 (R) on entry.  For HX_T_WLM, argmax_out_dev (int32
+   [batch], may be NULL) receives the greedy token; it must be NULL for the other kinds. */
+int hx_stage_linear(hx_engine *engine, int matrix_kind, int layer, int32_t batch, const float *x_dev,
+                    float *y_dev, int32_t *argmax_out_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEXDECODE_H */

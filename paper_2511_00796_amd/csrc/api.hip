@@ -1,0 +1,469 @@
+// The C ABI: argument validation, buffer maps, and the launch sequence of one decode step.
+// All device work is enqueued on the caller's stream; nothing here allocates device memory.
+#include "hx_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+// ---- errors ------------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int hx_fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" const char *hx_last_error(void) { return g_err; }
+
+// ---- configuration and maps --------------------------------------------------------------------------------------
+static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+static int env_int(const char *name, int dflt) {
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    return atoi(s);
+}
+
+static int check_config(const hx_model_config *c) {
+    if (!c) return hx_fail(HX_E_NULL, "config is NULL");
+    if (c->struct_size != sizeof(hx_model_config))
+        return hx_fail(HX_E_CONFIG, "struct_size %u, expected %zu", c->struct_size, sizeof(hx_model_config));
+    if (c->n_layers < 1 || c->vocab < 1) return hx_fail(HX_E_CONFIG, "n_layers and vocab must be positive");
+    if (c->head_dim != 64 && c->head_dim != 128) return hx_fail(HX_E_CONFIG, "head_dim %d: only 64 and 128", c->head_dim);
+    if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
+        return hx_fail(HX_E_CONFIG, "n_q_heads %d must be a positive multiple of n_kv_heads %d", c->n_q_heads, c->n_kv_heads);
+    if (c->n_q_heads / c->n_kv_heads > 16) return hx_fail(HX_E_CONFIG, "more than 16 query heads per KV head");
+    if (c->hidden < 32 || c->hidden % 32 != 0 || c->hidden > HX_MAX_HIDDEN)
+        return hx_fail(HX_E_CONFIG, "hidden %d must be a multiple of 32 in [32, %d]", c->hidden, HX_MAX_HIDDEN);
+    if (c->intermediate < 16 || c->intermediate % 16 != 0)
+        return hx_fail(HX_E_CONFIG, "intermediate %d must be a positive multiple of 16", c->intermediate);
+    if (c->vocab % 4 != 0) return hx_fail(HX_E_CONFIG, "vocab %d must be a multiple of 4", c->vocab);
+    if (c->block_size != HX_BLOCK_TOKENS) return hx_fail(HX_E_CONFIG, "block_size %d: only 16", c->block_size);
+    if (c->max_batch < 1 || c->max_batch > 256) return hx_fail(HX_E_CONFIG, "max_batch %d not in [1, 256]", c->max_batch);
+    if (c->max_seq_len < 1 || c->max_seq_len > (1 << 20)) return hx_fail(HX_E_CONFIG, "max_seq_len %d not in [1, 2^20]", c->max_seq_len);
+    if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return hx_fail(HX_E_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
+    return HX_OK;
+}
+
+static int attention_chunk() {
+    int c = env_int("HX_ATTN_CHUNK", 512);
+    if (c < 16) c = 16;
+    if (c > 1024) c = 1024;
+    return c / 16 * 16;
+}
+
+static int choose_splits(int k_steps, int n_tiles) {
+    int forced = env_int("HX_GEMM_SPLITS", 0);
+    int wgs = (n_tiles + 3) / 4;
+    int s = forced > 0 ? forced : (192 + wgs - 1) / wgs;
+    int cap = k_steps / 16;
+    if (s > 8) s = 8;
+    if (s > cap) s = cap;
+    if (s < 1) s = 1;
+    return s;
+}
+
+static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up, bool fused_epilogue) {
+    m->K = K;
+    m->N = gate_up ? 2 * N : N;
+    m->k_steps = K / 16;
+    m->n_tiles = gate_up ? N / 16 : (N + 31) / 32;
+    m->splits = fused_epilogue ? 1 : choose_splits(m->k_steps, m->n_tiles);
+    m->offset = *at;
+    *at = align_up(*at + (size_t)m->n_tiles * m->k_steps * 1024);
+}
+
+struct derived {
+    int G, D, q_dim, kv_dim, qkv_dim;
+};
+static derived derive(const hx_model_config *c) {
+    derived d;
+    d.D = c->head_dim;
+    d.G = c->n_q_heads / c->n_kv_heads;
+    d.q_dim = c->n_q_heads * c->head_dim;
+    d.kv_dim = c->n_kv_heads * c->head_dim;
+    d.qkv_dim = d.q_dim + 2 * d.kv_dim;
+    return d;
+}
+
+// fills e->layers (if not NULL), e->embed/gf/wlm and returns the total weight bytes
+static size_t map_weights(hx_engine *e) {
+    const hx_model_config *c = &e->cfg;
+    size_t at = 0;
+    for (int l = 0; l < c->n_layers; ++l) {
+        hx_layer_map tmp;
+        hx_layer_map *lm = e->layers ? &e->layers[l] : &tmp;
+        init_matrix(&lm->wqkv, &at, c->hidden, e->qkv_dim, false, false);
+        init_matrix(&lm->wo, &at, e->q_dim, c->hidden, false, false);
+        init_matrix(&lm->wgu, &at, c->hidden, c->intermediate, true, true);
+        init_matrix(&lm->wd, &at, c->intermediate, c->hidden, false, false);
+        lm->g1 = at; at = align_up(at + (size_t)c->hidden * 2);
+        lm->g2 = at; at = align_up(at + (size_t)c->hidden * 2);
+        lm->bqkv = at; at = align_up(at + (size_t)e->qkv_dim * 2);
+    }
+    e->embed = at; at = align_up(at + (size_t)c->vocab * c->hidden * 2);
+    e->gf = at; at = align_up(at + (size_t)c->hidden * 2);
+    init_matrix(&e->wlm, &at, c->hidden, c->vocab, false, true);
+    return at;
+}
+
+static size_t map_workspace(hx_engine *e) {
+    const hx_model_config *c = &e->cfg;
+    hx_ws_map *m = &e->map;
+    const size_t B = c->max_batch, MG = hx_m_groups(c->max_batch);
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+    m->x = take(B * c->hidden * 4);
+    m->xp = take((size_t)(c->hidden / 16) * MG * 1024);
+    m->ap = take((size_t)(e->q_dim / 16) * MG * 1024);
+    m->mp = take((size_t)(c->intermediate / 16) * MG * 1024);
+    size_t wide = (size_t)(e->qkv_dim > c->hidden ? e->qkv_dim : c->hidden);
+    m->ypart = take(8 * B * wide * 4);
+    m->qp = take(B * c->n_kv_heads * (size_t)(e->D / 32) * 1024);
+    m->cs = take(2 * B * (e->D / 2) * 4);
+    m->item_seq = take((size_t)e->max_items * 4);
+    m->item_chunk = take((size_t)e->max_items * 4);
+    m->first_item = take((B + 1) * 4);
+    m->n_items = take(256);
+    m->part_ml = take((size_t)e->max_items * c->n_kv_heads * 32 * 4);
+    m->part_o = take((size_t)e->max_items * c->n_kv_heads * e->G * e->D * 4);
+    m->amax_val = take(B * e->wlm.n_tiles * 4);
+    m->amax_idx = take(B * e->wlm.n_tiles * 4);
+    size_t widest = wide;
+    if ((size_t)c->intermediate > widest) widest = c->intermediate;
+    if ((size_t)e->q_dim > widest) widest = e->q_dim;
+    m->scratch_f32 = take(B * widest * 4);
+    m->total = at;
+    return at;
+}
+
+static int init_engine_shape(hx_engine *e, const hx_model_config *cfg) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    memset(e, 0, sizeof(*e));
+    e->cfg = *cfg;
+    derived d = derive(cfg);
+    e->G = d.G; e->D = d.D; e->q_dim = d.q_dim; e->kv_dim = d.kv_dim; e->qkv_dim = d.qkv_dim;
+    e->m_groups_max = hx_m_groups(cfg->max_batch);
+    e->chunk = attention_chunk();
+    e->max_items = cfg->max_batch * ((cfg->max_seq_len + e->chunk - 1) / e->chunk);
+    return HX_OK;
+}
+
+extern "C" int hx_weights_bytes(const hx_model_config *cfg, size_t *out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    hx_engine e;
+    int rc = init_engine_shape(&e, cfg);
+    if (rc) return rc;
+    *out = map_weights(&e);
+    return HX_OK;
+}
+
+extern "C" int hx_workspace_bytes(const hx_model_config *cfg, size_t *out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    hx_engine e;
+    int rc = init_engine_shape(&e, cfg);
+    if (rc) return rc;
+    map_weights(&e);
+    *out = map_workspace(&e);
+    return HX_OK;
+}
+
+extern "C" int hx_kv_bytes(const hx_model_config *cfg, int64_t num_blocks, size_t *out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (num_blocks < 1 || num_blocks > (int64_t)0x7fffffff) return hx_fail(HX_E_RANGE, "num_blocks %lld out of range", (long long)num_blocks);
+    *out = (size_t)cfg->n_layers * (size_t)num_blocks * cfg->n_kv_heads * 2 * (16 * (size_t)cfg->head_dim * 2);
+    return HX_OK;
+}
+
+static int check_dev_buffer(const void *p, size_t have, size_t need, const char *what) {
+    if (!p) return hx_fail(HX_E_NULL, "%s is NULL", what);
+    if (((uintptr_t)p & 255) != 0) return hx_fail(HX_E_ALIGN, "%s is not 256-byte aligned", what);
+    if (have < need) return hx_fail(HX_E_TOO_SMALL, "%s has %zu bytes, needs %zu", what, have, need);
+    return HX_OK;
+}
+
+extern "C" int hx_engine_create(const hx_model_config *cfg, void *weights_dev, size_t weights_bytes, void *workspace_dev,
+                                size_t workspace_bytes, hx_engine **out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    *out = nullptr;
+    hx_engine shape;
+    int rc = init_engine_shape(&shape, cfg);
+    if (rc) return rc;
+    hx_engine *e = new (std::nothrow) hx_engine(shape);
+    if (!e) return hx_fail(HX_E_HIP, "out of host memory");
+    e->layers = new (std::nothrow) hx_layer_map[cfg->n_layers];
+    if (!e->layers) { delete e; return hx_fail(HX_E_HIP, "out of host memory"); }
+    size_t wneed = map_weights(e);
+    size_t sneed = map_workspace(e);
+    if ((rc = check_dev_buffer(weights_dev, weights_bytes, wneed, "weights buffer")) ||
+        (rc = check_dev_buffer(workspace_dev, workspace_bytes, sneed, "workspace"))) {
+        delete[] e->layers;
+        delete e;
+        return rc;
+    }
+    e->weights = (char *)weights_dev;
+    e->ws = (char *)workspace_dev;
+    e->weights_bytes = weights_bytes;
+    e->ws_bytes = workspace_bytes;
+    *out = e;
+    return HX_OK;
+}
+
+extern "C" int hx_engine_destroy(hx_engine *e) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    delete[] e->layers;
+    delete e;
+    return HX_OK;
+}
+
+extern "C" int hx_attention_chunk(const hx_engine *e) { return e ? e->chunk : hx_fail(HX_E_NULL, "engine is NULL"); }
+
+extern "C" int hx_set_attn_capture(hx_engine *e, float *attn_dev) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    e->attn_capture = attn_dev;
+    return HX_OK;
+}
+
+// ---- weight packing ----------------------------------------------------------------------------------------------
+extern "C" int hx_weights_pack(hx_engine *e, int kind, int layer, const void *src, int64_t rows, int64_t cols, void *stream) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (!src) return hx_fail(HX_E_NULL, "src is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    const hx_model_config *c = &e->cfg;
+    const bool per_layer = !(kind == HX_T_EMBED || kind == HX_T_GF || kind == HX_T_WLM);
+    if (per_layer && (layer < 0 || layer >= c->n_layers)) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    const hx_layer_map *lm = per_layer ? &e->layers[layer] : nullptr;
+    auto want = [&](int64_t r, int64_t cc) -> int {
+        if (rows != r || cols != cc)
+            return hx_fail(HX_E_SHAPE, "tensor kind %d: got [%lld, %lld], expected [%lld, %lld]", kind, (long long)rows,
+                           (long long)cols, (long long)r, (long long)cc);
+        return HX_OK;
+    };
+    auto copy_vec = [&](size_t off, size_t n) -> int {
+        HX_CHECK_HIP(hipMemcpyAsync(e->weights + off, src, n * 2, hipMemcpyDeviceToDevice, st));
+        return HX_OK;
+    };
+    int rc;
+    switch (kind) {
+        case HX_T_EMBED: if ((rc = want(c->vocab, c->hidden))) return rc; return copy_vec(e->embed, (size_t)c->vocab * c->hidden);
+        case HX_T_GF:    if ((rc = want(c->hidden, 1)) && (rc = want(1, c->hidden))) return rc; return copy_vec(e->gf, c->hidden);
+        case HX_T_G1:    if ((rc = want(c->hidden, 1)) && (rc = want(1, c->hidden))) return rc; return copy_vec(lm->g1, c->hidden);
+        case HX_T_G2:    if ((rc = want(c->hidden, 1)) && (rc = want(1, c->hidden))) return rc; return copy_vec(lm->g2, c->hidden);
+        case HX_T_BQKV:  if ((rc = want(e->qkv_dim, 1)) && (rc = want(1, e->qkv_dim))) return rc; return copy_vec(lm->bqkv, e->qkv_dim);
+        case HX_T_WQKV:  if ((rc = want(c->hidden, e->qkv_dim))) return rc; return hx_launch_pack_matrix(e, &lm->wqkv, src, rows, cols, 0, st);
+        case HX_T_WO:    if ((rc = want(e->q_dim, c->hidden))) return rc; return hx_launch_pack_matrix(e, &lm->wo, src, rows, cols, 0, st);
+        case HX_T_WG:    if ((rc = want(c->hidden, c->intermediate))) return rc; return hx_launch_pack_matrix(e, &lm->wgu, src, rows, cols, 1, st);
+        case HX_T_WU:    if ((rc = want(c->hidden, c->intermediate))) return rc; return hx_launch_pack_matrix(e, &lm->wgu, src, rows, cols, 2, st);
+        case HX_T_WD:    if ((rc = want(c->intermediate, c->hidden))) return rc; return hx_launch_pack_matrix(e, &lm->wd, src, rows, cols, 0, st);
+        case HX_T_WLM:   if ((rc = want(c->hidden, c->vocab))) return rc; return hx_launch_pack_matrix(e, &e->wlm, src, rows, cols, 0, st);
+        default: return hx_fail(HX_E_SHAPE, "unknown tensor kind %d", kind);
+    }
+}
+
+// ---- KV cache ------------------------------------------------------------------------------------------------------
+extern "C" int kv_alloc(hx_engine *e, void *kv_dev, size_t kv_bytes, int64_t num_blocks, hx_kv **out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    *out = nullptr;
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    size_t need;
+    int rc = hx_kv_bytes(&e->cfg, num_blocks, &need);
+    if (rc) return rc;
+    if ((rc = check_dev_buffer(kv_dev, kv_bytes, need, "kv pool"))) return rc;
+    hx_kv *kv = new (std::nothrow) hx_kv;
+    if (!kv) return hx_fail(HX_E_HIP, "out of host memory");
+    kv->engine = e;
+    kv->pool = (char *)kv_dev;
+    kv->num_blocks = num_blocks;
+    kv->tile_bytes = 16 * (size_t)e->D * 2;
+    kv->block_bytes = (size_t)e->cfg.n_kv_heads * 2 * kv->tile_bytes;
+    kv->layer_bytes = (size_t)num_blocks * kv->block_bytes;
+    *out = kv;
+    return HX_OK;
+}
+
+extern "C" int kv_free(hx_kv *kv) {
+    if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
+    delete kv;
+    return HX_OK;
+}
+
+static int check_table_args(const hx_kv *kv, int layer, const void *a, const void *b, const void *c, const void *d,
+                            int32_t max_blocks, int32_t batch) {
+    if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
+    if (!a || !b || !c || !d) return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    if (layer < 0 || layer >= kv->engine->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    if (batch < 1) return hx_fail(HX_E_RANGE, "batch %d must be positive", batch);
+    if (max_blocks < 1) return hx_fail(HX_E_RANGE, "max_blocks_per_seq %d must be positive", max_blocks);
+    return HX_OK;
+}
+
+extern "C" int prefill_fill(hx_kv *kv, int layer, const void *k_dev, const void *v_dev, const int32_t *seq_start_dev,
+                            const int32_t *block_table_dev, int32_t max_blocks, int32_t batch, int64_t total_tokens,
+                            void *stream) {
+    int rc = check_table_args(kv, layer, k_dev, v_dev, seq_start_dev, block_table_dev, max_blocks, batch);
+    if (rc) return rc;
+    if (total_tokens < 0) return hx_fail(HX_E_RANGE, "total_tokens negative");
+    return hx_launch_kv_scatter(kv, layer, k_dev, v_dev, seq_start_dev, block_table_dev, max_blocks, batch, total_tokens,
+                                false, (hipStream_t)stream);
+}
+
+extern "C" int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_dev, const int32_t *seq_start_dev,
+                            const int32_t *block_table_dev, int32_t max_blocks, int32_t batch, int64_t total_tokens,
+                            void *stream) {
+    int rc = check_table_args(kv, layer, k_out_dev, v_out_dev, seq_start_dev, block_table_dev, max_blocks, batch);
+    if (rc) return rc;
+    if (total_tokens < 0) return hx_fail(HX_E_RANGE, "total_tokens negative");
+    return hx_launch_kv_scatter(kv, layer, k_out_dev, v_out_dev, seq_start_dev, block_table_dev, max_blocks, batch,
+                                total_tokens, true, (hipStream_t)stream);
+}
+
+// ---- the decode step -------------------------------------------------------------------------------------------------
+static int check_step_args(const hx_engine *e, const hx_kv *kv, int32_t batch, int32_t max_blocks) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (kv && kv->engine != e) return hx_fail(HX_E_SHAPE, "kv belongs to another engine");
+    if (batch < 1 || batch > e->cfg.max_batch) return hx_fail(HX_E_RANGE, "batch %d not in [1, max_batch %d]", batch, e->cfg.max_batch);
+    if (max_blocks < 1) return hx_fail(HX_E_RANGE, "max_blocks_per_seq %d must be positive", max_blocks);
+    return HX_OK;
+}
+
+extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                           const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
+                           int32_t *next_tokens_out, void *stream) {
+    int rc = check_step_args(e, kv, batch, max_blocks);
+    if (rc) return rc;
+    if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
+    if (!tokens || !positions || !seq_lens || !block_table || !next_tokens_out)
+        return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    const hx_model_config *c = &e->cfg;
+    char *ws = e->ws;
+    float *ypart = (float *)(ws + e->map.ypart);
+    const size_t attn_stride = (size_t)batch * e->q_dim;
+
+    if ((rc = hx_launch_step_setup(e, batch, positions, seq_lens, st))) return rc;
+    if ((rc = hx_launch_embed_norm(e, batch, tokens, e->layers[0].g1, st))) return rc;
+    for (int l = 0; l < c->n_layers; ++l) {
+        const hx_layer_map *lm = &e->layers[l];
+        if ((rc = hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+        if ((rc = hx_launch_rope_append(e, kv, l, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim, positions,
+                                        block_table, max_blocks, st))) return rc;
+        if ((rc = hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks,
+                                      e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st))) return rc;
+        if ((rc = hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+        if ((rc = hx_launch_reduce_norm(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, lm->g2, st))) return rc;
+        if ((rc = hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st))) return rc;
+        if ((rc = hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+        const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
+        if ((rc = hx_launch_reduce_norm(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, next_gain, st))) return rc;
+    }
+    if ((rc = hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st))) return rc;
+    return hx_launch_argmax_final(e, batch, next_tokens_out, st);
+}
+
+// ---- single stages ---------------------------------------------------------------------------------------------------
+extern "C" int hx_stage_worklist(hx_engine *e, int32_t batch, const int32_t *seq_lens, int32_t *n_items_out,
+                                 int32_t *item_seq_out, int32_t *item_chunk_out, int32_t *first_item_out, void *stream) {
+    int rc = check_step_args(e, nullptr, batch, 1);
+    if (rc) return rc;
+    if (!seq_lens || !n_items_out || !item_seq_out || !item_chunk_out || !first_item_out)
+        return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
+    const size_t items = (size_t)batch * ((e->cfg.max_seq_len + e->chunk - 1) / e->chunk);
+    HX_CHECK_HIP(hipMemcpyAsync(n_items_out, e->ws + e->map.n_items, 4, hipMemcpyDeviceToDevice, st));
+    HX_CHECK_HIP(hipMemcpyAsync(item_seq_out, e->ws + e->map.item_seq, items * 4, hipMemcpyDeviceToDevice, st));
+    HX_CHECK_HIP(hipMemcpyAsync(item_chunk_out, e->ws + e->map.item_chunk, items * 4, hipMemcpyDeviceToDevice, st));
+    HX_CHECK_HIP(hipMemcpyAsync(first_item_out, e->ws + e->map.first_item, ((size_t)batch + 1) * 4, hipMemcpyDeviceToDevice, st));
+    return HX_OK;
+}
+
+extern "C" int hx_stage_rope_append(hx_engine *e, hx_kv *kv, int layer, int32_t batch, const float *qkv_dev,
+                                    const int32_t *positions, const int32_t *block_table, int32_t max_blocks,
+                                    float *q_out_dev, void *stream) {
+    int rc = check_step_args(e, kv, batch, max_blocks);
+    if (rc) return rc;
+    if (!kv || !qkv_dev || !positions || !block_table || !q_out_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = hx_launch_step_setup(e, batch, positions, nullptr, st))) return rc;
+    if ((rc = hx_launch_rope_append(e, kv, layer, batch, qkv_dev, 1, 0, positions, block_table, max_blocks, st))) return rc;
+    return hx_launch_unpack_q(e, batch, q_out_dev, st);
+}
+
+extern "C" int hx_stage_attention(hx_engine *e, hx_kv *kv, int layer, int32_t batch, const float *q_dev,
+                                  const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks,
+                                  float *out_dev, void *stream) {
+    int rc = check_step_args(e, kv, batch, max_blocks);
+    if (rc) return rc;
+    if (!kv || !q_dev || !seq_lens || !block_table || !out_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = hx_launch_pack_q(e, batch, q_dev, st))) return rc;
+    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
+    return hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, out_dev, st);
+}
+
+extern "C" int hx_stage_rmsnorm(hx_engine *e, int gain_kind, int layer, int32_t batch, const float *x_dev, float *y_dev,
+                                void *stream) {
+    int rc = check_step_args(e, nullptr, batch, 1);
+    if (rc) return rc;
+    if (!x_dev || !y_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    size_t off;
+    if (gain_kind == HX_T_GF) off = e->gf;
+    else {
+        if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+        if (gain_kind == HX_T_G1) off = e->layers[layer].g1;
+        else if (gain_kind == HX_T_G2) off = e->layers[layer].g2;
+        else return hx_fail(HX_E_SHAPE, "tensor kind %d is not a gain", gain_kind);
+    }
+    return hx_launch_norm_only(e, batch, x_dev, off, y_dev, (hipStream_t)stream);
+}
+
+extern "C" int hx_stage_linear(hx_engine *e, int kind, int layer, int32_t batch, const float *x_dev, float *y_dev,
+                               int32_t *argmax_out_dev, void *stream) {
+    int rc = check_step_args(e, nullptr, batch, 1);
+    if (rc) return rc;
+    if (!x_dev || !y_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (kind != HX_T_WLM && argmax_out_dev) return hx_fail(HX_E_SHAPE, "argmax_out_dev only with HX_T_WLM");
+    if (kind != HX_T_WLM && (layer < 0 || layer >= e->cfg.n_layers)) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    hipStream_t st = (hipStream_t)stream;
+    const hx_model_config *c = &e->cfg;
+    char *ws = e->ws;
+    float *ypart = (float *)(ws + e->map.ypart);
+    const hx_layer_map *lm = (kind == HX_T_WLM) ? nullptr : &e->layers[layer];
+    switch (kind) {
+        case HX_T_WQKV:
+            if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
+            if ((rc = hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+            return hx_launch_sum_partials(e, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim, e->qkv_dim, y_dev, st);
+        case HX_T_WO:
+            if ((rc = hx_launch_pack_x(e, batch, x_dev, e->q_dim, ws + e->map.ap, st))) return rc;
+            if ((rc = hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+            return hx_launch_sum_partials(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, c->hidden, y_dev, st);
+        case HX_T_WG:
+            if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
+            if ((rc = hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st))) return rc;
+            return hx_launch_unpack_x(e, batch, ws + e->map.mp, c->intermediate, y_dev, st);
+        case HX_T_WD:
+            if ((rc = hx_launch_pack_x(e, batch, x_dev, c->intermediate, ws + e->map.mp, st))) return rc;
+            if ((rc = hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+            return hx_launch_sum_partials(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, c->hidden, y_dev, st);
+        case HX_T_WLM:
+            if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
+            if ((rc = hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, y_dev, nullptr, st))) return rc;
+            if (argmax_out_dev) return hx_launch_argmax_final(e, batch, argmax_out_dev, st);
+            return HX_OK;
+        default:
+            return hx_fail(HX_E_SHAPE, "tensor kind %d is not a matrix", kind);
+    }
+}

@@ -1,0 +1,277 @@
+// Split-K flash-decoding attention over the paged cache, the work-list builder that flattens the
+// ragged batch into fixed-size KV chunks, and the combine kernel that merges the chunk partials.
+//
+// One wavefront owns one (sequence, KV head, chunk) item and serves all G query heads of that KV
+// head at once, so every K and V byte is read exactly once:
+//     S^T[token, g] = K_tile[token, :] . q[g, :]        v_mfma_f32_16x16x32_bf16 (A = K tile, B = packed q)
+//     O^T[d, g]    += V_tile^T[d, token] . P^T[token, g] v_mfma_f32_16x16x16_bf16 (A = V tile, B = P)
+// The accumulator layout of the first product (lane = query head g, 4 registers = 4 tokens) is
+// exactly the B-operand layout of the second, so the probabilities never cross lanes; only the
+// running maximum is exchanged between the four 16-lane groups with two wavefront shuffles per
+// tile, and the running sum is reduced once at the end.  K/V tiles are stored in operand order
+// in the pool, so they go from HBM to registers with contiguous 1-KiB loads and need no LDS.
+#include "hx_internal.h"
+
+#define HX_NEG_BIG (-1.0e30f)
+
+// ---- per-step setup: work list + RoPE angles -------------------------------------------------------------
+// block 0: items.  Sequence b contributes ceil(T_b / chunk) items (b, c) in batch order.
+// blocks 1..batch: cos/sin of pos * theta^(-2i/D), evaluated in double, stored fp32.
+__global__ __launch_bounds__(256) void step_setup_kernel(int batch, int chunk, const int32_t *__restrict__ positions,
+                                                         const int32_t *__restrict__ seq_lens,
+                                                         int32_t *__restrict__ item_seq, int32_t *__restrict__ item_chunk,
+                                                         int32_t *__restrict__ first_item, int32_t *__restrict__ n_items,
+                                                         float *__restrict__ cs, int half, double theta, int max_batch) {
+    if (blockIdx.x == 0) {
+        __shared__ int32_t scan[256];
+        int b = threadIdx.x;
+        int cnt = 0;
+        if (seq_lens != nullptr && b < batch) cnt = (seq_lens[b] + chunk - 1) / chunk;
+        scan[b] = cnt;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {       // inclusive Hillis-Steele scan
+            int v = (b >= off) ? scan[b - off] : 0;
+            __syncthreads();
+            scan[b] += v;
+            __syncthreads();
+        }
+        if (seq_lens != nullptr) {
+            int start = scan[b] - cnt;
+            if (b < batch) {
+                first_item[b] = start;
+                for (int c = 0; c < cnt; ++c) { item_seq[start + c] = b; item_chunk[start + c] = c; }
+            }
+            if (b == batch - 1) { first_item[batch] = scan[b]; n_items[0] = scan[b]; }
+        }
+    } else if (positions != nullptr) {
+        int b = blockIdx.x - 1;
+        double pos = (double)positions[b];
+        for (int i = threadIdx.x; i < half; i += blockDim.x) {
+            double ang = pos * pow(theta, -(double)i / (double)half);
+            cs[(size_t)b * half + i] = (float)cos(ang);
+            cs[(size_t)max_batch * half + (size_t)b * half + i] = (float)sin(ang);
+        }
+    }
+}
+
+int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
+                         hipStream_t st) {
+    char *ws = e->ws;
+    hipLaunchKernelGGL(step_setup_kernel, dim3(batch + 1), dim3(256), 0, st, batch, e->chunk, positions, seq_lens,
+                       (int32_t *)(ws + e->map.item_seq), (int32_t *)(ws + e->map.item_chunk),
+                       (int32_t *)(ws + e->map.first_item), (int32_t *)(ws + e->map.n_items),
+                       (float *)(ws + e->map.cs), e->D / 2, (double)e->cfg.rope_theta, e->cfg.max_batch);
+    HX_CHECK_LAUNCH("step_setup");
+    return HX_OK;
+}
+
+// ---- split-K attention -----------------------------------------------------------------------------------
+template <int D>
+struct KvRegs {
+    uint4 k[D / 32];
+    uint4 v[D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void load_tile(KvRegs<D> &r, const char *pool_layer, size_t block_bytes, int32_t blk,
+                                          size_t head_off, int lane) {
+    const uint4 *p = (const uint4 *)(pool_layer + (size_t)blk * block_bytes + head_off) + lane;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) r.k[i] = p[i * 64];
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) r.v[i] = p[(D / 32 + i) * 64];
+}
+
+// PF = tiles in flight per wavefront (register ring).
+template <int D, int PF>
+__global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict__ pool_layer, size_t block_bytes,
+                                                         const uint16_t *__restrict__ qp,
+                                                         const int32_t *__restrict__ seq_lens,
+                                                         const int32_t *__restrict__ table, int max_blocks,
+                                                         const int32_t *__restrict__ item_seq,
+                                                         const int32_t *__restrict__ item_chunk,
+                                                         const int32_t *__restrict__ n_items, int chunk, int n_kv,
+                                                         int G, float scale_log2e, float *__restrict__ part_ml,
+                                                         float *__restrict__ part_o) {
+    const int item = blockIdx.y;
+    if (item >= n_items[0]) return;
+    const int kvh = blockIdx.x;    // the KV heads of a block are adjacent in the pool: launch them together
+    const int lane = threadIdx.x;
+    const int g = lane & 15, qd = lane >> 4;
+    const int b = item_seq[item], c = item_chunk[item];
+    const int T = seq_lens[b];
+    const int t0 = c * chunk;
+    const int t1 = min(T, t0 + chunk);
+    const int nblk = (t1 - t0 + 15) >> 4;          // 1 .. chunk/16 (<= 64)
+    const size_t head_off = (size_t)kvh * 2 * (16 * D * 2);
+
+    // physical ids of this chunk's blocks: lane i holds block i
+    int32_t my_blk = 0;
+    if (lane < nblk) my_blk = table[(size_t)b * max_blocks + (t0 >> 4) + lane];
+
+    // packed query: B operand of the score product
+    bf16x8_t qop[D / 32];
+    {
+        const uint4 *q4 = (const uint4 *)(qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512) + lane;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) qop[kk] = __builtin_bit_cast(bf16x8_t, q4[kk * 64]);
+    }
+
+    f32x4_t o[D / 16];
+#pragma unroll
+    for (int nn = 0; nn < D / 16; ++nn) o[nn] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m = HX_NEG_BIG;   // running maximum of the scaled scores (base-2 domain), same in the 4 lane groups
+    float l = 0.f;          // this lane's share of the running sum
+
+    KvRegs<D> ring[PF];
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+        if (s < nblk) load_tile<D>(ring[s], pool_layer, block_bytes, __builtin_amdgcn_readlane(my_blk, s), head_off, lane);
+
+    for (int base = 0; base < nblk; base += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            const int i = base + s;
+            if (i < nblk) {                                   // wave-uniform
+                KvRegs<D> cur = ring[s];
+                if (i + PF < nblk)
+                    load_tile<D>(ring[s], pool_layer, block_bytes, __builtin_amdgcn_readlane(my_blk, i + PF), head_off, lane);
+
+                // scores of 16 tokens x 16 query heads
+                f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk)
+                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[kk]), qop[kk], sc, 0, 0, 0);
+                const int tok0 = t0 + i * 16 + qd * 4;     // this lane's 4 tokens
+                float s4[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
+                // positions past the end of the sequence: their V must not reach the product as NaN/Inf
+                if (i == nblk - 1 && (t1 & 15) != 0) {
+                    const int valid = t1 - tok0;              // tokens of this lane group that exist
+                    uint32_t m01 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+                    uint32_t m23 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+                    for (int q = 0; q < D / 32; ++q) {
+                        cur.v[q].x &= m01; cur.v[q].y &= m23; cur.v[q].z &= m01; cur.v[q].w &= m23;
+                    }
+                }
+                float mx = fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                float p[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s4[r] - m_new);
+                l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+                m = m_new;
+#pragma unroll
+                for (int nn = 0; nn < D / 16; ++nn) o[nn] *= alpha;
+                uint2 pk;
+                pk.x = hx_pack_bf16x2(p[0], p[1]);
+                pk.y = hx_pack_bf16x2(p[2], p[3]);
+                const s16x4_t pop = __builtin_bit_cast(s16x4_t, pk);
+#pragma unroll
+                for (int q = 0; q < D / 32; ++q) {
+                    uint2 lo = make_uint2(cur.v[q].x, cur.v[q].y), hi = make_uint2(cur.v[q].z, cur.v[q].w);
+                    o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop, o[2 * q], 0, 0, 0);
+                    o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop, o[2 * q + 1], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // total of the running sum over the four lane groups
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    const size_t pi = (size_t)item * n_kv + kvh;
+    if (qd == 0) {
+        part_ml[pi * 32 + g] = m;
+        part_ml[pi * 32 + 16 + g] = l;
+    }
+    if (g < G) {
+        float *po = part_o + (pi * G + g) * D;
+#pragma unroll
+        for (int nn = 0; nn < D / 16; ++nn) *(f32x4_t *)(po + nn * 16 + qd * 4) = o[nn];
+    }
+}
+
+// ---- combine ---------------------------------------------------------------------------------------------
+// o = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of the sequence, in chunk order.
+// One thread per (sequence, query head, 8 consecutive d); writes the bf16-rounded result into the
+// packed activation buffer of the output projection and, if asked, the unrounded fp32 values.
+template <int D>
+__global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, int n_kv, int G,
+                                                           const int32_t *__restrict__ first_item,
+                                                           const float *__restrict__ part_ml,
+                                                           const float *__restrict__ part_o,
+                                                           uint16_t *__restrict__ ap, int m_groups,
+                                                           float *__restrict__ attn_f32) {
+    constexpr int TPH = D / 8;                       // threads per head
+    int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    int d8 = gid % TPH;
+    int bh = gid / TPH;
+    if (bh >= batch * n_q) return;
+    int b = bh / n_q, h = bh % n_q;
+    int kvh = h / G, g = h % G;
+    int i0 = first_item[b], i1 = first_item[b + 1];
+    float M = HX_NEG_BIG;
+    for (int it = i0; it < i1; ++it) M = fmaxf(M, part_ml[((size_t)it * n_kv + kvh) * 32 + g]);
+    float den = 0.f;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    for (int it = i0; it < i1; ++it) {
+        size_t pi = (size_t)it * n_kv + kvh;
+        float w = exp2f(part_ml[pi * 32 + g] - M);
+        den += w * part_ml[pi * 32 + 16 + g];
+        const float *po = part_o + (pi * G + g) * D + d8 * 8;
+        f32x4_t a = *(const f32x4_t *)po, c = *(const f32x4_t *)(po + 4);
+        acc[0] += w * a[0]; acc[1] += w * a[1]; acc[2] += w * a[2]; acc[3] += w * a[3];
+        acc[4] += w * c[0]; acc[5] += w * c[1]; acc[6] += w * c[2]; acc[7] += w * c[3];
+    }
+    float inv = 1.0f / den;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] *= inv;
+    if (attn_f32) {
+        float *dst = attn_f32 + ((size_t)b * n_q + h) * D + d8 * 8;
+        *(f32x4_t *)dst = f32x4_t{acc[0], acc[1], acc[2], acc[3]};
+        *(f32x4_t *)(dst + 4) = f32x4_t{acc[4], acc[5], acc[6], acc[7]};
+    }
+    uint4 pk;
+    pk.x = hx_pack_bf16x2(acc[0], acc[1]); pk.y = hx_pack_bf16x2(acc[2], acc[3]);
+    pk.z = hx_pack_bf16x2(acc[4], acc[5]); pk.w = hx_pack_bf16x2(acc[6], acc[7]);
+    *(uint4 *)(ap + hx_xp_index(b, h * D + d8 * 8, m_groups)) = pk;
+}
+
+int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
+                        const int32_t *table, int max_blocks, float *attn_f32_out, hipStream_t st) {
+    const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
+    char *ws = e->ws;
+    const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
+    const int max_items = batch * ((e->cfg.max_seq_len + e->chunk - 1) / e->chunk);
+    const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
+    dim3 grid(n_kv, max_items), block(64);
+#define HX_ATTN_ARGS                                                                                             \
+    pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), seq_lens, table, max_blocks,                \
+        (const int32_t *)(ws + e->map.item_seq), (const int32_t *)(ws + e->map.item_chunk),                      \
+        (const int32_t *)(ws + e->map.n_items), e->chunk, n_kv, e->G, scale_log2e,                               \
+        (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
+    if (e->D == 128) hipLaunchKernelGGL((attn_splitk_kernel<128, 3>), grid, block, 0, st, HX_ATTN_ARGS);
+    else             hipLaunchKernelGGL((attn_splitk_kernel<64, 4>), grid, block, 0, st, HX_ATTN_ARGS);
+#undef HX_ATTN_ARGS
+    HX_CHECK_LAUNCH("attn_splitk");
+
+    const int m_groups = hx_m_groups(batch);
+    const int threads = batch * n_q * (e->D / 8);
+    dim3 cgrid((threads + 255) / 256), cblock(256);
+#define HX_COMB_ARGS                                                                                             \
+    batch, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.first_item), (const float *)(ws + e->map.part_ml),     \
+        (const float *)(ws + e->map.part_o), (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out
+    if (e->D == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, cblock, 0, st, HX_COMB_ARGS);
+    else             hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, cblock, 0, st, HX_COMB_ARGS);
+#undef HX_COMB_ARGS
+    HX_CHECK_LAUNCH("attn_combine");
+    return HX_OK;
+}

@@ -1,0 +1,177 @@
+// Internal declarations shared by the translation units of libhexdecode.so (gfx950 only).
+//
+// Data layouts (all chosen so that one wavefront load instruction -- 64 lanes x 16 bytes --
+// covers 1 KiB of contiguous memory and lands directly in matrix-core operand order):
+//
+//  * packed weight matrix W [K, N] -> [n_tile][k_step][lane 0..63][8 bf16]:
+//        element (lane, j) = W[16*k_step + 8*(lane/32) + j][32*n_tile + lane%32]
+//    i.e. the A operand (32 rows n x 16 k) of v_mfma_f32_32x32x16_bf16; columns >= N are zero.
+//    The gate and up projections share one packed matrix with 16 gate columns followed by the
+//    16 matching up columns in every n_tile, so both land in the same lane of the accumulator.
+//
+//  * packed activations X [M, K] (bf16) -> [k_step][m_group][lane][8 bf16]:
+//        element (lane, j) = X[32*m_group + lane%32][16*k_step + 8*(lane/32) + j]
+//    i.e. the B operand (16 k x 32 columns m) of the same instruction.
+//
+//  * packed query of one (sequence, KV head): [kk][lane][8 bf16], kk < head_dim/32:
+//        element (lane, j) = q[head = kvh*G + lane%16][32*kk + 8*(lane/16) + j], zero for lane%16 >= G
+//    i.e. the B operand (32 k x 16 columns g) of v_mfma_f32_16x16x32_bf16.
+//
+//  * KV pool: [layer][block][kv_head][K tile | V tile]; a tile holds 16 tokens x head_dim:
+//      K tile [kk][lane][8]:  (lane, j) = K[token lane%16][32*kk + 8*(lane/16) + j]
+//                             (A operand, 16 tokens x 32 k, of v_mfma_f32_16x16x32_bf16)
+//      V tile [i][lane][8]:   (lane, 4*half + jj) = V[token 4*(lane/16) + jj][32*i + 16*half + lane%16]
+//                             (two A operands, 16 rows d x 16 k tokens, of v_mfma_f32_16x16x16_bf16)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/hexdecode.h"
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+#define HX_WAVE 64
+#define HX_BLOCK_TOKENS 16
+#define HX_MAX_HIDDEN 8192
+
+// ---- error reporting (api.hip) -------------------------------------------------------------------
+int hx_fail(int code, const char *fmt, ...);
+#define HX_CHECK_HIP(expr)                                                                         \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return hx_fail(HX_E_HIP, "%s: %s", #expr, hipGetErrorString(e_));    \
+    } while (0)
+#define HX_CHECK_LAUNCH(name)                                                                      \
+    do {                                                                                           \
+        hipError_t e_ = hipGetLastError();                                                         \
+        if (e_ != hipSuccess) return hx_fail(HX_E_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- small device helpers ------------------------------------------------------------------------
+__device__ __forceinline__ float hx_bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// round-to-nearest-even on the upper half of the fp32 pattern (finite inputs)
+__device__ __forceinline__ uint16_t hx_f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t hx_pack_bf16x2(float lo, float hi) {
+    return (uint32_t)hx_f32_to_bf16(lo) | ((uint32_t)hx_f32_to_bf16(hi) << 16);
+}
+
+// m-groups (of 32 rows) of the packed activation buffers for a batch: rounded up to 1, 2, 4 or 8 so that
+// producers and the matrix products agree on one layout per batch size
+__host__ __device__ __forceinline__ int hx_m_groups(int batch) {
+    int g = (batch + 31) / 32;
+    return g <= 1 ? 1 : (g <= 2 ? 2 : (g <= 4 ? 4 : 8));
+}
+
+// element offset (in bf16) of activation (m, k) inside a packed X buffer with m_groups groups
+__host__ __device__ __forceinline__ size_t hx_xp_index(int m, int k, int m_groups) {
+    int ks = k >> 4, h = (k >> 3) & 1, j = k & 7;
+    return (((size_t)ks * m_groups + (m >> 5)) * 64 + (h * 32 + (m & 31))) * 8 + j;
+}
+
+// element offsets (in bf16) inside one K / V tile of 16 tokens x head_dim
+__host__ __device__ __forceinline__ int hx_ktile_index(int t, int d) {
+    return (d >> 5) * 512 + ((((d >> 3) & 3) * 16 + t) << 3) + (d & 7);
+}
+__host__ __device__ __forceinline__ int hx_vtile_index(int t, int d) {
+    return (d >> 5) * 512 + ((((t >> 2) * 16) + (d & 15)) << 3) + (((d >> 4) & 1) << 2) + (t & 3);
+}
+
+// ---- host-side descriptors ------------------------------------------------------------------------
+
+struct hx_matrix {          // one packed weight matrix
+    size_t offset;          // byte offset in the weight buffer
+    int K, N;               // logical shape
+    int k_steps, n_tiles;   // K / 16, ceil(N / 32) (gate|up: intermediate / 16)
+    int splits;             // K-splits used by the streaming product (1 when the epilogue is fused)
+};
+
+struct hx_layer_map {
+    hx_matrix wqkv, wo, wgu, wd;
+    size_t g1, g2, bqkv;    // byte offsets of bf16 vectors
+};
+
+struct hx_ws_map {          // byte offsets in the workspace
+    size_t x;               // fp32 [max_batch, hidden]            residual stream
+    size_t xp;              // bf16 packed [hidden/16][MG][64][8]  normalised activations
+    size_t ap;              // bf16 packed [q_dim/16][MG][64][8]   attention output
+    size_t mp;              // bf16 packed [inter/16][MG][64][8]   SwiGLU output
+    size_t ypart;           // fp32 [max_splits][max_batch][max(qkv_dim, hidden)] product partials
+    size_t qp;              // bf16 packed queries [max_batch][n_kv][D/32][64][8]
+    size_t cs;              // fp32 [max_batch][D/2] cos, then [max_batch][D/2] sin
+    size_t item_seq, item_chunk, first_item, n_items;   // int32 work list
+    size_t part_ml;         // fp32 [max_items][n_kv][32]   running max (16) | sum (16)
+    size_t part_o;          // fp32 [max_items][n_kv][G][D] unnormalised partial outputs
+    size_t amax_val, amax_idx;  // fp32 / int32 [max_batch][lm n_tiles]
+    size_t scratch_f32;     // fp32 [max_batch][max(hidden, q_dim, inter, qkv_dim)] stage-hook staging
+    size_t total;
+};
+
+struct hx_engine {
+    hx_model_config cfg;
+    int G, D, q_dim, kv_dim, qkv_dim;
+    int m_groups_max;       // ceil(max_batch / 32)
+    int chunk;              // tokens per split-K attention item
+    int max_items;          // max_batch * ceil(max_seq_len / chunk)
+    char *weights;          // device
+    char *ws;               // device
+    size_t weights_bytes, ws_bytes;
+    hx_layer_map *layers;   // [n_layers], host
+    size_t embed, gf;       // byte offsets
+    hx_matrix wlm;
+    hx_ws_map map;
+    float *attn_capture;    // device or NULL
+};
+
+struct hx_kv {
+    hx_engine *engine;
+    char *pool;             // device
+    int64_t num_blocks;
+    size_t tile_bytes;      // 16 * head_dim * 2
+    size_t block_bytes;     // n_kv_heads * 2 * tile_bytes
+    size_t layer_bytes;     // num_blocks * block_bytes
+};
+
+// ---- kernel launchers (one per translation unit) ---------------------------------------------------
+
+// kv_cache.hip
+int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *v, const int32_t *seq_start,
+                         const int32_t *table, int max_blocks, int batch, int64_t total_tokens, bool gather,
+                         hipStream_t st);
+int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int batch, const float *ypart,
+                          int splits, size_t split_stride, const int32_t *positions, const int32_t *table,
+                          int max_blocks, hipStream_t st);
+
+// attention.hip
+int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
+                         hipStream_t st);
+int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
+                        const int32_t *table, int max_blocks, float *attn_f32_out, hipStream_t st);
+
+// gemm.hip
+int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *src, int64_t rows, int64_t cols,
+                          int col_phase /*0 plain, 1 gate, 2 up*/, hipStream_t st);
+enum { HX_EPI_PARTIAL = 0, HX_EPI_SWIGLU = 1, HX_EPI_LOGITS = 2 };
+int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue,
+                   float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st);
+int hx_launch_argmax_final(const hx_engine *e, int batch, int32_t *tokens_out, hipStream_t st);
+
+// elementwise.hip
+int hx_launch_embed_norm(const hx_engine *e, int batch, const int32_t *tokens, size_t gain_off, hipStream_t st);
+int hx_launch_reduce_norm(const hx_engine *e, int batch, const float *ypart, int splits, size_t split_stride,
+                          size_t gain_off, hipStream_t st);
+int hx_launch_pack_x(const hx_engine *e, int batch, const float *x, int K, void *xp, hipStream_t st);
+int hx_launch_unpack_x(const hx_engine *e, int batch, const void *xp, int K, float *x, hipStream_t st);
+int hx_launch_unpack_q(const hx_engine *e, int batch, float *q_out, hipStream_t st);
+int hx_launch_pack_q(const hx_engine *e, int batch, const float *q, hipStream_t st);
+int hx_launch_sum_partials(const hx_engine *e, int batch, const float *ypart, int splits, size_t split_stride,
+                           int N, float *y, hipStream_t st);
+int hx_launch_norm_only(const hx_engine *e, int batch, const float *x, size_t gain_off, float *y, hipStream_t st);
