@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout decode step on one MI355X.
+
+A "step" is one pass of the whole hot path (work list, embedding, every layer's norms, products,
+RoPE + cache append, split-K attention and combine, LM head, argmax) over one batch of synthetic
+sequences whose weights and KV cache are already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b-b128] [--breakdown]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def cpu_baseline(wl, dw_host, sample_rows, sample_layers):
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: `sample_rows`
+    sequences through `sample_layers` layers plus embedding and LM head, then scale the per-layer
+    time to the full depth.  Returns the JSON object."""
+    import dataclasses
+
+    import numpy as np
+
+    import oracle
+    s = wl.shape
+    rows = dw_host["rows"]
+    sub = dataclasses.replace(s, n_layers=sample_layers)
+    cfg = oracle.make_config(sub)
+    w = oracle.Weights(dw_host["globals"], dw_host["layers"])
+    ctx, table = dw_host["ctx"][rows], dw_host["table_rows"]
+    kv = oracle.PagedKV(cfg, dw_host["num_blocks"])
+    start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
+    for l in range(sample_layers):
+        kv.fill(l, dw_host["k"][l], dw_host["v"][l], start, table)
+    toks = dw_host["tokens"][rows]
+    t0 = time.perf_counter()
+    oracle.decode_step(cfg, w, kv, toks, ctx, ctx + 1, table)
+    t_layers = time.perf_counter() - t0
+    cfg0 = oracle.make_config(dataclasses.replace(s, n_layers=0))
+    t0 = time.perf_counter()
+    oracle.decode_step(cfg0, w, kv, toks, ctx, ctx + 1, table)
+    t_head = time.perf_counter() - t0
+    per_layer = max(t_layers - t_head, 0.0) / sample_layers
+    full = per_layer * s.n_layers + t_head
+    return {"value": len(rows) / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d sequences (shortest, longest, seeded random) through %d of %d layers + embedding and "
+                      "LM head, %.1f s of CPU work; per-layer time scaled to %d layers"
+                      % (len(rows), wl.batch, sample_layers, s.n_layers, t_layers + t_head, s.n_layers)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7b-b128")
+    ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=32)
+    ap.add_argument("--cpu-layers", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the decode step has no cross-GPU path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2511_00796_amd import binding, synth, workload
+
+    binding.load()
+    wl = synth.WORKLOADS[args.workload]
+    s = wl.shape
+    ctx = synth.context_lengths(wl)
+
+    # rows and layers the CPU baseline will recompute (copied to the host while the workload is built)
+    host = None
+    if not args.no_cpu_baseline:
+        rows = {int(np.argmin(ctx)), int(np.argmax(ctx))}
+        rng = np.random.default_rng(wl.seed)
+        while len(rows) < min(args.cpu_rows, wl.batch):
+            rows.add(int(rng.integers(0, wl.batch)))
+        rows = np.array(sorted(rows))
+        seq_start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int64)
+        nblk = (ctx[rows].astype(np.int64) + 1 + 15) // 16
+        width = int(nblk.max())
+        table_rows = np.full((len(rows), width), -1, dtype=np.int32)
+        at = 0
+        for i, n in enumerate(nblk):
+            table_rows[i, :n] = np.arange(at, at + n)
+            at += int(n)
+        host = {"rows": rows, "ctx": ctx, "layers": [], "k": [], "v": [], "table_rows": table_rows, "num_blocks": at,
+                "tokens": synth.token_ids(wl, wl.batch)}
+
+        def tap(kind, layer, t):
+            if kind == "globals":
+                host["globals"] = {k: synth.as_u16(v) for k, v in t.items()}
+            elif layer < args.cpu_layers:
+                if kind == "layer":
+                    host["layers"].append({k: synth.as_u16(v) for k, v in t.items()})
+                else:
+                    for name in ("k", "v"):
+                        host[name].append(np.concatenate(
+                            [synth.as_u16(t[name][seq_start[r]: seq_start[r] + ctx[r]]) for r in rows]))
+    else:
+        tap = None
+
+    t_build = time.perf_counter()
+    dw = workload.build(wl, tap=tap)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
+    eng = dw.engine
+    nbytes = dw.bytes()
+
+    for _ in range(args.warmup):
+        dw.step()
+    torch.cuda.synchronize()
+    eng.profile_enable(["attention"])          # HIP events around the dominant kernel only
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dw.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    attn_ms, attn_n = eng.profile_read("attention")
+    eng.profile_enable([])
+
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = wl.batch / (dt / args.steps)
+    kv_bytes_per_launch = nbytes["kv"] / s.n_layers
+    attn_avg_ms = attn_ms / max(attn_n, 1)
+    achieved = kv_bytes_per_launch / (attn_avg_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "decode tokens/s on 1 MI355X (7B, batch 128) + % of HBM peak GB/s",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
+                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_chunk": eng.attention_chunk()},
+        "step_hbm": {"algorithmic_bytes": nbytes["total"], "weights_bytes": nbytes["weights"], "kv_bytes": nbytes["kv"],
+                     "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
+                     "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": "attn_splitk_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launches_timed": int(attn_n), "avg_launch_ms": attn_avg_ms,
+                     "algorithmic_bytes_per_launch": kv_bytes_per_launch},
+        "setup_s": t_build,
+    }
+
+    if args.breakdown:
+        eng.profile_enable(binding.KERNEL_CLASSES)
+        for _ in range(3):
+            dw.step()
+        torch.cuda.synchronize()
+        bd = {}
+        for k in binding.KERNEL_CLASSES:
+            ms, n = eng.profile_read(k)
+            bd[k] = {"ms_per_step": ms / 3, "launches_per_step": n // 3}
+        eng.profile_enable([])
+        out["breakdown"] = bd
+
+    if host is not None:
+        out["cpu_baseline"] = cpu_baseline(wl, host, args.cpu_rows, args.cpu_layers)
+        out["cpu_baseline"]["gpu_over_cpu"] = tokens_per_s / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

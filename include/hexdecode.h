@@ -14,7 +14,7 @@
  * Numeric contract.  Weights, KV cache and every matrix-product input are bf16; all arithmetic
  * accumulates in fp32; the residual stream stays fp32.  Activations are rounded to bf16
  * (nearest-even) at the five matrix-product inputs, at the rotated query and at K/V cache
- * writes, nowhere else (softmax probabilities may be rounded to bf16 inside the P*V product).
+ * writes, nowhere else (softmax probabilities enter the P*V product as a high + low bf16 pair).
  *
  * Conventions for every function.
  *   - extern "C"; returns hx_status: 0 on success, negative on error.  Never throws, never aborts.
@@ -199,6 +199,32 @@ int hx_stage_rmsnorm(hx_engine *engine, int gain_kind, int layer, int32_t batch,
    [batch], may be NULL) receives the greedy token; it must be NULL for the other kinds. */
 int hx_stage_linear(hx_engine *engine, int matrix_kind, int layer, int32_t batch, const float *x_dev,
                     float *y_dev, int32_t *argmax_out_dev, void *stream);
+
+/* ---- per-kernel timing (measurement hook) -------------------------------------------------------------- */
+
+/* Kernel classes of the decode step. */
+typedef enum {
+    HX_K_ATTENTION = 0, /* split-K attention kernel                      */
+    HX_K_COMBINE = 1,   /* split-K combine                               */
+    HX_K_GEMM_QKV = 2,
+    HX_K_GEMM_O = 3,
+    HX_K_GEMM_GATE_UP = 4,
+    HX_K_GEMM_DOWN = 5,
+    HX_K_GEMM_LM = 6,
+    HX_K_NORM = 7,      /* embedding / split-sum + residual + RMSNorm    */
+    HX_K_ROPE = 8,      /* bias + RoPE + cache append                    */
+    HX_K_SETUP = 9,     /* work list, RoPE angles, final argmax          */
+    HX_K_COUNT = 10
+} hx_kernel_class;
+
+/* While bit k of `class_mask` is set, every launch of kernel class k made by decode_step is bracketed
+   by two HIP events recorded on the step's stream (host objects; no device memory is allocated).
+   0 switches timing off.  Bracketing adds a few microseconds per launch, so a throughput measurement
+   should time at most the one class it reports. */
+int hx_profile_enable(hx_engine *engine, uint32_t class_mask);
+/* Waits for the recorded events, adds up the elapsed time of class `kernel_class` since the last read,
+   releases those events.  HOST out-pointers. */
+int hx_profile_read(hx_engine *engine, int kernel_class, double *total_ms_out, int64_t *launches_out);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,11 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
            "decode_step", "hx_set_attn_capture", "hx_stage_worklist", "hx_attention_chunk",
-           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear"]
+           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
+           "hx_profile_enable", "hx_profile_read"]
+
+KERNEL_CLASSES = ["attention", "combine", "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm", "norm",
+                  "rope_append", "setup"]
 
 
 class ModelConfig(C.Structure):
@@ -73,6 +77,8 @@ def load():
         "hx_stage_attention": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],
         "hx_stage_linear": [vp, C.c_int, C.c_int, i32, vp, vp, vp, vp],
+        "hx_profile_enable": [vp, C.c_uint32],
+        "hx_profile_read": [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     }
     for name, args in sig.items():
         f = getattr(L, name)
@@ -175,6 +181,19 @@ class Engine:
     def set_attn_capture(self, buf: Optional[torch.Tensor]) -> None:
         self._capture = buf
         _check(load().hx_set_attn_capture(self.handle, _ptr(buf)))
+
+    # -- per-kernel timing
+    def profile_enable(self, classes) -> None:
+        mask = 0
+        for c in classes:
+            mask |= 1 << (KERNEL_CLASSES.index(c) if isinstance(c, str) else int(c))
+        _check(load().hx_profile_enable(self.handle, mask))
+
+    def profile_read(self, klass):
+        k = KERNEL_CLASSES.index(klass) if isinstance(klass, str) else int(klass)
+        ms, n = C.c_double(), C.c_int64()
+        _check(load().hx_profile_read(self.handle, k, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     # -- single stages
     def attention_chunk(self) -> int:

@@ -59,15 +59,28 @@ static int attention_chunk() {
     return c / 16 * 16;
 }
 
-static int choose_splits(int k_steps, int n_tiles) {
-    int forced = env_int("HX_GEMM_SPLITS", 0);
-    int wgs = (n_tiles + 3) / 4;
-    int s = forced > 0 ? forced : (192 + wgs - 1) / wgs;
-    int cap = k_steps / 16;
+// Shape of the streaming product for one matrix: wn x wk wavefronts per workgroup and `splits` K-splits
+// over workgroups.  Wide matrices (gate|up, LM head) take 4 n-tiles per workgroup and the whole K, so the
+// epilogue can be fused; narrow ones (q/k/v, output, down projection) need K-parallelism to occupy 256
+// compute units: 2 x 2 wavefronts plus enough splits for about two workgroups per compute unit, bounded
+// so that each k-slice keeps at least 16 k-steps.  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
+static void choose_product_shape(hx_matrix *m, bool fused_epilogue) {
+    m->wn = 4; m->wk = 1; m->splits = 1;
+    if (fused_epilogue) return;
+    m->wn = 2; m->wk = 2;
+    int wgs = (m->n_tiles + m->wn - 1) / m->wn;
+    int s = (384 + wgs - 1) / wgs;
+    int cap = m->k_steps / (16 * m->wk);
     if (s > 8) s = 8;
     if (s > cap) s = cap;
     if (s < 1) s = 1;
-    return s;
+    m->splits = s;
+    const char *ov = getenv("HX_GEMM_SHAPE");
+    int a, b, c;
+    if (ov && sscanf(ov, "%d,%d,%d", &a, &b, &c) == 3 && ((a == 4 && b == 1) || (a == 2 && b == 2) || (a == 1 && b == 4)) &&
+        c >= 1 && c <= 8 && m->k_steps / (b * c) >= 1) {
+        m->wn = a; m->wk = b; m->splits = c;
+    }
 }
 
 static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up, bool fused_epilogue) {
@@ -75,7 +88,7 @@ static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up, bo
     m->N = gate_up ? 2 * N : N;
     m->k_steps = K / 16;
     m->n_tiles = gate_up ? N / 16 : (N + 31) / 32;
-    m->splits = fused_epilogue ? 1 : choose_splits(m->k_steps, m->n_tiles);
+    choose_product_shape(m, fused_epilogue);
     m->offset = *at;
     *at = align_up(*at + (size_t)m->n_tiles * m->k_steps * 1024);
 }
@@ -126,7 +139,8 @@ static size_t map_workspace(hx_engine *e) {
     m->mp = take((size_t)(c->intermediate / 16) * MG * 1024);
     size_t wide = (size_t)(e->qkv_dim > c->hidden ? e->qkv_dim : c->hidden);
     m->ypart = take(8 * B * wide * 4);
-    m->qp = take(B * c->n_kv_heads * (size_t)(e->D / 32) * 1024);
+    m->qp = take(B * c->n_kv_heads * (size_t)(e->D / 32) * 1024 + 16 * (size_t)e->D * 2);   // + one K tile of slack: the attention
+                                                                                          // kernel may read a whole K|V tile starting at any query
     m->cs = take(2 * B * (e->D / 2) * 4);
     m->item_seq = take((size_t)e->max_items * 4);
     m->item_chunk = take((size_t)e->max_items * 4);
@@ -215,12 +229,19 @@ extern "C" int hx_engine_create(const hx_model_config *cfg, void *weights_dev, s
     e->ws = (char *)workspace_dev;
     e->weights_bytes = weights_bytes;
     e->ws_bytes = workspace_bytes;
+    e->profile_mask = 0;
+    e->profile_events = new (std::nothrow) std::vector<std::pair<hipEvent_t, hipEvent_t>>[HX_K_COUNT];
     *out = e;
     return HX_OK;
 }
 
 extern "C" int hx_engine_destroy(hx_engine *e) {
     if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (e->profile_events) {
+        for (int k = 0; k < HX_K_COUNT; ++k)
+            for (auto &p : e->profile_events[k]) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+        delete[] e->profile_events;
+    }
     delete[] e->layers;
     delete e;
     return HX_OK;
@@ -327,6 +348,51 @@ extern "C" int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_d
                                 total_tokens, true, (hipStream_t)stream);
 }
 
+// ---- per-kernel timing ---------------------------------------------------------------------------------------------
+struct timed_launch {   // brackets one launch with two events when its class is selected
+    hx_engine *e; int k; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+    timed_launch(hx_engine *e_, int k_, hipStream_t st_) : e(e_), k(k_), st(st_) {
+        if (e->profile_events && (e->profile_mask >> k) & 1u) {
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+            (void)hipEventRecord(a, st);
+        }
+    }
+    ~timed_launch() {
+        if (a) { (void)hipEventRecord(b, st); e->profile_events[k].push_back({a, b}); }
+    }
+};
+#define HX_TIMED(klass, call) do { timed_launch t_(e, klass, st); if ((rc = (call))) return rc; } while (0)
+
+extern "C" int hx_profile_enable(hx_engine *e, uint32_t class_mask) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (class_mask >> HX_K_COUNT) return hx_fail(HX_E_RANGE, "class_mask has bits beyond HX_K_COUNT");
+    e->profile_mask = class_mask;
+    return HX_OK;
+}
+
+extern "C" int hx_profile_read(hx_engine *e, int kernel_class, double *total_ms_out, int64_t *launches_out) {
+    if (!e || !total_ms_out || !launches_out) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (kernel_class < 0 || kernel_class >= HX_K_COUNT) return hx_fail(HX_E_RANGE, "kernel class %d out of range", kernel_class);
+    double total = 0.0;
+    int64_t n = 0;
+    if (e->profile_events) {
+        auto &v = e->profile_events[kernel_class];
+        for (auto &p : v) {
+            HX_CHECK_HIP(hipEventSynchronize(p.second));
+            float ms = 0.f;
+            HX_CHECK_HIP(hipEventElapsedTime(&ms, p.first, p.second));
+            total += ms;
+            ++n;
+            (void)hipEventDestroy(p.first);
+            (void)hipEventDestroy(p.second);
+        }
+        v.clear();
+    }
+    *total_ms_out = total;
+    *launches_out = n;
+    return HX_OK;
+}
+
 // ---- the decode step -------------------------------------------------------------------------------------------------
 static int check_step_args(const hx_engine *e, const hx_kv *kv, int32_t batch, int32_t max_blocks) {
     if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
@@ -350,24 +416,25 @@ extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t
     float *ypart = (float *)(ws + e->map.ypart);
     const size_t attn_stride = (size_t)batch * e->q_dim;
 
-    if ((rc = hx_launch_step_setup(e, batch, positions, seq_lens, st))) return rc;
-    if ((rc = hx_launch_embed_norm(e, batch, tokens, e->layers[0].g1, st))) return rc;
+    HX_TIMED(HX_K_SETUP, hx_launch_step_setup(e, batch, positions, seq_lens, st));
+    HX_TIMED(HX_K_NORM, hx_launch_embed_norm(e, batch, tokens, e->layers[0].g1, st));
     for (int l = 0; l < c->n_layers; ++l) {
         const hx_layer_map *lm = &e->layers[l];
-        if ((rc = hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
-        if ((rc = hx_launch_rope_append(e, kv, l, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim, positions,
-                                        block_table, max_blocks, st))) return rc;
-        if ((rc = hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks,
-                                      e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st))) return rc;
-        if ((rc = hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
-        if ((rc = hx_launch_reduce_norm(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, lm->g2, st))) return rc;
-        if ((rc = hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st))) return rc;
-        if ((rc = hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
+        HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st));
+        HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim,
+                                                 positions, block_table, max_blocks, st));
+        HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
+        HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st));
+        HX_TIMED(HX_K_GEMM_O, hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st));
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, lm->g2, st));
+        HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st));
+        HX_TIMED(HX_K_GEMM_DOWN, hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st));
         const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
-        if ((rc = hx_launch_reduce_norm(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, next_gain, st))) return rc;
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, next_gain, st));
     }
-    if ((rc = hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st))) return rc;
-    return hx_launch_argmax_final(e, batch, next_tokens_out, st);
+    HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st));
+    HX_TIMED(HX_K_SETUP, hx_launch_argmax_final(e, batch, next_tokens_out, st));
+    return HX_OK;
 }
 
 // ---- single stages ---------------------------------------------------------------------------------------------------
@@ -410,7 +477,8 @@ extern "C" int hx_stage_attention(hx_engine *e, hx_kv *kv, int layer, int32_t ba
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hx_launch_pack_q(e, batch, q_dev, st))) return rc;
     if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
-    return hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, out_dev, st);
+    if ((rc = hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, st))) return rc;
+    return hx_launch_combine(e, batch, out_dev, st);
 }
 
 extern "C" int hx_stage_rmsnorm(hx_engine *e, int gain_kind, int layer, int32_t batch, const float *x_dev, float *y_dev,

@@ -66,23 +66,22 @@ int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions
 }
 
 // ---- split-K attention -----------------------------------------------------------------------------------
-template <int D>
-struct KvRegs {
-    uint4 k[D / 32];
-    uint4 v[D / 32];
-};
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
+// One K/V tile in registers: D/32 K operands then D/32 V operands, 16 bytes per lane each.
+// K/V are read exactly once per step: non-temporal loads keep them from displacing reusable lines.
 template <int D>
-__device__ __forceinline__ void load_tile(KvRegs<D> &r, const char *pool_layer, size_t block_bytes, int32_t blk,
-                                          size_t head_off, int lane) {
-    const uint4 *p = (const uint4 *)(pool_layer + (size_t)blk * block_bytes + head_off) + lane;
+__device__ __forceinline__ void load_tile(u32x4_t (&r)[D / 16], const char *tile, int lane) {
+    const u32x4_t *p = (const u32x4_t *)tile + lane;
 #pragma unroll
-    for (int i = 0; i < D / 32; ++i) r.k[i] = p[i * 64];
-#pragma unroll
-    for (int i = 0; i < D / 32; ++i) r.v[i] = p[(D / 32 + i) * 64];
+    for (int i = 0; i < D / 16; ++i) r[i] = __builtin_nontemporal_load(p + i * 64);
 }
 
-// PF = tiles in flight per wavefront (register ring).
+// PF = tiles in flight per wavefront (register ring).  The loop has no prologue and no conditional load:
+// it starts PF tiles early (those iterations see only masked-out tokens and zero operands) and every
+// iteration requests the tile PF ahead into the slot it has just finished with; past the end of the
+// chunk the request goes to the packed query (small, cache-resident, finite), so the load stream is
+// unconditional and the compiler keeps exactly PF - 1 tiles outstanding behind every wait.
 template <int D, int PF>
 __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict__ pool_layer, size_t block_bytes,
                                                          const uint16_t *__restrict__ qp,
@@ -110,9 +109,10 @@ __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict_
     if (lane < nblk) my_blk = table[(size_t)b * max_blocks + (t0 >> 4) + lane];
 
     // packed query: B operand of the score product
+    const char *qtile = (const char *)(qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512);
     bf16x8_t qop[D / 32];
     {
-        const uint4 *q4 = (const uint4 *)(qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512) + lane;
+        const uint4 *q4 = (const uint4 *)qtile + lane;
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) qop[kk] = __builtin_bit_cast(bf16x8_t, q4[kk * 64]);
     }
@@ -123,62 +123,75 @@ __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict_
     float m = HX_NEG_BIG;   // running maximum of the scaled scores (base-2 domain), same in the 4 lane groups
     float l = 0.f;          // this lane's share of the running sum
 
-    KvRegs<D> ring[PF];
+    u32x4_t ring[PF][D / 16];
 #pragma unroll
     for (int s = 0; s < PF; ++s)
-        if (s < nblk) load_tile<D>(ring[s], pool_layer, block_bytes, __builtin_amdgcn_readlane(my_blk, s), head_off, lane);
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) ring[s][i] = u32x4_t{0u, 0u, 0u, 0u};
 
-    for (int base = 0; base < nblk; base += PF) {
+    const int n_rounds = (nblk + PF - 1) / PF + 1;
+    for (int rd = 0; rd < n_rounds; ++rd) {
 #pragma unroll
         for (int s = 0; s < PF; ++s) {
-            const int i = base + s;
-            if (i < nblk) {                                   // wave-uniform
-                KvRegs<D> cur = ring[s];
-                if (i + PF < nblk)
-                    load_tile<D>(ring[s], pool_layer, block_bytes, __builtin_amdgcn_readlane(my_blk, i + PF), head_off, lane);
-
-                // scores of 16 tokens x 16 query heads
-                f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            const int i = (rd - 1) * PF + s;                   // tile of this iteration; < 0 while the ring fills
+            const int tok0 = t0 + i * 16 + qd * 4;             // this lane's 4 tokens
+            // scores of 16 tokens x 16 query heads
+            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < D / 32; ++kk)
-                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[kk]), qop[kk], sc, 0, 0, 0);
-                const int tok0 = t0 + i * 16 + qd * 4;     // this lane's 4 tokens
-                float s4[4];
+            for (int kk = 0; kk < D / 32; ++kk)
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ring[s][kk]), qop[kk], sc, 0, 0, 0);
+            float s4[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
-                // positions past the end of the sequence: their V must not reach the product as NaN/Inf
-                if (i == nblk - 1 && (t1 & 15) != 0) {
-                    const int valid = t1 - tok0;              // tokens of this lane group that exist
-                    uint32_t m01 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
-                    uint32_t m23 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+            for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r >= t0 && tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
+            // V of positions that do not exist must not reach the product as NaN/Inf
+            u32x4_t vv[D / 32];
 #pragma unroll
-                    for (int q = 0; q < D / 32; ++q) {
-                        cur.v[q].x &= m01; cur.v[q].y &= m23; cur.v[q].z &= m01; cur.v[q].w &= m23;
-                    }
-                }
-                float mx = fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m, mx);
-                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-                float p[4];
+            for (int q = 0; q < D / 32; ++q) vv[q] = ring[s][D / 32 + q];
+            if (i < 0 || t0 + (i + 1) * 16 > t1) {             // wave-uniform: a tile with missing tokens
+                const int valid = (i < 0) ? 0 : (t1 - tok0);
+                const uint32_t m01 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+                const uint32_t m23 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s4[r] - m_new);
-                l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-                m = m_new;
-#pragma unroll
-                for (int nn = 0; nn < D / 16; ++nn) o[nn] *= alpha;
-                uint2 pk;
-                pk.x = hx_pack_bf16x2(p[0], p[1]);
-                pk.y = hx_pack_bf16x2(p[2], p[3]);
-                const s16x4_t pop = __builtin_bit_cast(s16x4_t, pk);
-#pragma unroll
-                for (int q = 0; q < D / 32; ++q) {
-                    uint2 lo = make_uint2(cur.v[q].x, cur.v[q].y), hi = make_uint2(cur.v[q].z, cur.v[q].w);
-                    o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop, o[2 * q], 0, 0, 0);
-                    o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop, o[2 * q + 1], 0, 0, 0);
-                }
+                for (int q = 0; q < D / 32; ++q) { vv[q].x &= m01; vv[q].y &= m23; vv[q].z &= m01; vv[q].w &= m23; }
             }
+            float mx = fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            float p[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s4[r] - m_new);
+            l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+            m = m_new;
+#pragma unroll
+            for (int nn = 0; nn < D / 16; ++nn) o[nn] *= alpha;
+            // P enters the matrix core as bf16; split it into a high and a low bf16 part so that the
+            // product keeps ~16 significant bits of every probability
+            uint2 ph, pl;
+            ph.x = hx_cvt_pk_bf16(p[0], p[1]);
+            ph.y = hx_cvt_pk_bf16(p[2], p[3]);
+            pl.x = hx_cvt_pk_bf16(p[0] - __uint_as_float(ph.x << 16), p[1] - __uint_as_float(ph.x & 0xffff0000u));
+            pl.y = hx_cvt_pk_bf16(p[2] - __uint_as_float(ph.y << 16), p[3] - __uint_as_float(ph.y & 0xffff0000u));
+            const s16x4_t pop_hi = __builtin_bit_cast(s16x4_t, ph);
+            const s16x4_t pop_lo = __builtin_bit_cast(s16x4_t, pl);
+#pragma unroll
+            for (int q = 0; q < D / 32; ++q) {
+                uint2 lo = make_uint2(vv[q].x, vv[q].y), hi = make_uint2(vv[q].z, vv[q].w);
+                o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_hi, o[2 * q], 0, 0, 0);
+                o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_hi, o[2 * q + 1], 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < D / 32; ++q) {
+                uint2 lo = make_uint2(vv[q].x, vv[q].y), hi = make_uint2(vv[q].z, vv[q].w);
+                o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_lo, o[2 * q], 0, 0, 0);
+                o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_lo, o[2 * q + 1], 0, 0, 0);
+            }
+            // the slot is free: request tile i + PF into it (or the query once the chunk is exhausted)
+            const int nx = i + PF;
+            const int32_t blk = __builtin_amdgcn_readlane(my_blk, nx & 63);
+            const char *src = (nx < nblk) ? pool_layer + (size_t)blk * block_bytes + head_off : qtile;
+            load_tile<D>(ring[s], src, lane);
         }
     }
     // total of the running sum over the four lane groups
@@ -246,10 +259,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
 }
 
 int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
-                        const int32_t *table, int max_blocks, float *attn_f32_out, hipStream_t st) {
+                        const int32_t *table, int max_blocks, hipStream_t st) {
     const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     char *ws = e->ws;
-    const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
+    const int n_kv = e->cfg.n_kv_heads;
     const int max_items = batch * ((e->cfg.max_seq_len + e->chunk - 1) / e->chunk);
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
     dim3 grid(n_kv, max_items), block(64);
@@ -262,7 +275,12 @@ int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batc
     else             hipLaunchKernelGGL((attn_splitk_kernel<64, 4>), grid, block, 0, st, HX_ATTN_ARGS);
 #undef HX_ATTN_ARGS
     HX_CHECK_LAUNCH("attn_splitk");
+    return HX_OK;
+}
 
+int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st) {
+    char *ws = e->ws;
+    const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
     const int m_groups = hx_m_groups(batch);
     const int threads = batch * n_q * (e->D / 8);
     dim3 cgrid((threads + 255) / 256), cblock(256);

@@ -51,12 +51,18 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 }
 
 // ---- the streaming product ------------------------------------------------------------------------------------
-template <int MG> struct GemmCfg { static constexpr int KC = (MG == 8) ? 4 : 8; };   // k-steps per LDS chunk
+// Workgroup = WN x WK consumer wavefronts + 1 producer wavefront.  Consumers: WN adjacent n-tiles, each
+// split into WK k-slices that are summed in slice order through LDS at the end; every consumer keeps
+// RING weight loads (1 KiB each, non-temporal) in flight in a register ring and issues no other
+// vector-memory load, so the in-order load counter never makes it wait for anything but the tile it is
+// about to use.  The producer copies the activations of the next chunks (KC k-steps per k-slice) from
+// L2 into a three-stage LDS buffer; one workgroup barrier per chunk hands them over.
+#define HX_GEMM_RING 16
 
 struct GemmArgs {
     const uint4 *wp;      // packed weights
     const uint4 *xp;      // packed activations
-    int k_steps, n_tiles, steps_per_split;
+    int k_steps, n_tiles, steps_per_split, steps_per_wave;
     int M, N;
     float *y;             // PARTIAL: [splits][M][N]; LOGITS: [M][N] or NULL
     size_t split_stride;  // elements between splits of y
@@ -65,18 +71,91 @@ struct GemmArgs {
     int32_t *amax_idx;
 };
 
-template <int MG, int EPI>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs a) {
-    constexpr int KC = GemmCfg<MG>::KC;
-    constexpr int XV = KC * MG / 4;                      // uint4 per thread per staged chunk
-    __shared__ uint4 xs[2][KC * MG * 64];
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t hx_stream_load(const uint4 *p) {   // read-once data: non-temporal
+    return __builtin_nontemporal_load((const u32x4_t *)p);
+}
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nt = blockIdx.x * 4 + wave;
-    const bool active = nt < a.n_tiles;                  // inactive wavefronts still stage activations
-    const int ks0 = blockIdx.y * a.steps_per_split;
-    const int ks1 = min(a.k_steps, ks0 + a.steps_per_split);
-    const int n_chunks = (ks1 - ks0 + KC - 1) / KC;
+// s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
+#define HX_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+template <int MG, int WN, int WK, int EPI>
+__global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
+    const uint4 *__restrict__ a_wp, const uint4 *__restrict__ a_xp, int a_k_steps, int a_n_tiles, int a_steps_per_split,
+    int a_steps_per_wave, int a_M, int a_N, float *__restrict__ a_y, size_t a_split_stride, uint16_t *__restrict__ a_mp,
+    float *__restrict__ a_amax_val, int32_t *__restrict__ a_amax_idx) {
+    constexpr int RING = HX_GEMM_RING;
+    constexpr int NBUF = 4;
+    constexpr int KCMG = 16 / WK;                                    // KiB of activations per k-slice buffer
+    constexpr int KC = (KCMG / MG) > 8 ? 8 : ((KCMG / MG) < 1 ? 1 : (KCMG / MG));   // k-steps per LDS chunk
+    constexpr int CPR = RING / KC;                                   // chunks per ring revolution
+    constexpr int SLICE_U4 = KC * MG * 64;
+    constexpr int PV = WK * KC * MG;                                 // 1-KiB copies per chunk (producer)
+    static_assert(RING % KC == 0, "ring must hold whole chunks");
+    static_assert(2 * PV <= 63, "two chunks of copies must fit the load counter");
+    static_assert((WK - 1) * WN * MG * 4 <= NBUF * WK * KC * MG, "reduction scratch must fit the activation buffers");
+    __shared__ u32x4_t xs[NBUF][WK][SLICE_U4];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform, kept in a scalar register
+    const bool producer = wave == WN * WK;               // the last wavefront only stages activations
+    const int wn = wave % WN, wk = producer ? 0 : wave / WN;
+    const int nt = blockIdx.x * WN + wn;
+    const bool active = !producer && nt < a_n_tiles;
+    const int split0 = blockIdx.y * a_steps_per_split;
+    const int split1 = min(a_k_steps, split0 + a_steps_per_split);
+    // every wavefront of the grid runs the same number of chunks: whole ring revolutions.  Steps past the end
+    // of a k-slice re-read the slice's last (cached) weight tile and skip the multiply, so the load stream
+    // carries no condition and the compiler keeps exactly RING - 1 loads outstanding.
+    const int n_chunks = (a_steps_per_wave + RING - 1) / RING * CPR;
+
+    if (producer) {
+        // k-slice w of this workgroup covers k-steps [split0 + w*spw, min(split1, +spw)); chunk c of it is a
+        // contiguous run of the packed activations, copied L2 -> LDS without passing through registers.
+        // Chunks c+1 .. c+3 are in flight or ready while the consumers work on chunk c.
+        const u32x4_t *xp4 = (const u32x4_t *)a_xp;
+        const int last_u4 = a_k_steps * MG * 64 - 1;
+        // virtual chunk v is real chunk max(v - CPR, 0): the consumers spend their first ring revolution
+        // multiplying zeros (ring not filled yet) with chunk 0, then fall into step with the real chunks
+        auto copy_chunk = [&](int v) {
+            const int buf = v % NBUF;
+            const int c = max(v - CPR, 0);
+#pragma unroll
+            for (int w = 0; w < WK; ++w) {
+                const int kb = min(split1, split0 + w * a_steps_per_wave);
+                const int base = (kb + c * KC) * MG * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < KC * MG; ++i)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void __attribute__((address_space(1))) *)(xp4 + min(base + i * 64, last_u4)),
+                        (void __attribute__((address_space(3))) *)&xs[buf][w][i * 64], 16, 0, 0);
+            }
+        };
+        const int n_virtual = n_chunks + CPR;
+        copy_chunk(0);
+        copy_chunk(1);
+        copy_chunk(2);
+        __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * PV));        // chunk 0 has landed
+        __syncthreads();
+        for (int v = 0; v < n_virtual; ++v) {
+            if (v + 3 < n_virtual) {
+                copy_chunk(v + 3);                            // into the buffer the consumers left at the last barrier
+                __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * PV)); // chunk v + 1 has landed
+            } else {
+                __builtin_amdgcn_s_waitcnt(HX_VMCNT(0));      // nothing is in flight once the loop ends
+            }
+            __syncthreads();
+        }
+        if (WK > 1) __syncthreads();
+        return;
+    }
+
+    const int kb0 = split0 + wk * a_steps_per_wave;                  // this wavefront's k-slice [kb0, ke)
+    const int ke = min(split1, kb0 + a_steps_per_wave);
+    const int n_valid = active ? max(0, ke - kb0) : 0;               // steps that are multiplied
+    const int kb = min(kb0, a_k_steps - 1);
+    const int last = max(0, min(a_k_steps, kb + a_steps_per_wave) - kb - 1);   // last step whose tile may be read
+    const uint4 *wrow = a_wp + ((size_t)(active ? nt : 0) * a_k_steps + kb) * 64 + lane;
 
     f32x16_t acc[MG];
 #pragma unroll
@@ -84,79 +163,85 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
 
-    const uint4 *wrow = a.wp + ((size_t)(active ? nt : 0) * a.k_steps) * 64 + lane;
-    uint4 wcur[KC], wnxt[KC], xr[XV];
+    // The ring starts as zeros and the loop starts one revolution early (c0 = -CPR): that revolution
+    // multiplies zeros while it requests the first RING tiles; from then on step s multiplies the tile
+    // requested RING steps earlier and immediately requests the tile of step s + RING into the same slot.
+    // There is no separate prologue, so the only loads outstanding at any wait are the ring's own, in order.
+    u32x4_t ring[RING];
+#pragma unroll
+    for (int r = 0; r < RING; ++r) ring[r] = u32x4_t{0u, 0u, 0u, 0u};
+    __syncthreads();
 
-    auto load_w = [&](uint4 *w, int ci) {
-        const int s0 = ks0 + ci * KC;
+    for (int c0 = -CPR; c0 < n_chunks; c0 += CPR) {
 #pragma unroll
-        for (int s = 0; s < KC; ++s)
-            if (active && s0 + s < ks1) w[s] = wrow[(size_t)(s0 + s) * 64];
-    };
-    auto load_x = [&](int ci) {
-        const int s0 = ks0 + ci * KC;
-        const int n_u4 = (min(ks1, s0 + KC) - s0) * MG * 64;
-        const uint4 *src = a.xp + (size_t)s0 * MG * 64;
+        for (int cc = 0; cc < CPR; ++cc) {
+            const int c = c0 + cc;
+            const u32x4_t *xb = &xs[(c + CPR) % NBUF][wk][lane];
+            // B operands are read from LDS one k-step ahead of the multiplies that use them
+            u32x4_t bcur[MG], bnxt[MG];
 #pragma unroll
-        for (int i = 0; i < XV; ++i)
-            if (tid + i * 256 < n_u4) xr[i] = src[tid + i * 256];
-    };
-    auto store_x = [&](int ci, int buf) {
-        const int s0 = ks0 + ci * KC;
-        const int n_u4 = (min(ks1, s0 + KC) - s0) * MG * 64;
+            for (int g = 0; g < MG; ++g) bcur[g] = xb[g * 64];
 #pragma unroll
-        for (int i = 0; i < XV; ++i)
-            if (tid + i * 256 < n_u4) xs[buf][tid + i * 256] = xr[i];
-    };
-    auto compute = [&](const uint4 *w, int ci, int buf) {
-        const int steps = min(ks1, ks0 + (ci + 1) * KC) - (ks0 + ci * KC);
+            for (int j = 0; j < KC; ++j) {
+                const int s = c * KC + j;
+                if (j + 1 < KC) {
 #pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            if (s < steps) {
-                const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, w[s]);
+                    for (int g = 0; g < MG; ++g) bnxt[g] = xb[((j + 1) * MG + g) * 64];
+                }
+                if (s < n_valid) {
+                    const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
 #pragma unroll
-                for (int g = 0; g < MG; ++g) {
-                    const bf16x8_t bop = __builtin_bit_cast(bf16x8_t, xs[buf][(s * MG + g) * 64 + lane]);
-                    acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop, acc[g], 0, 0, 0);
+                    for (int g = 0; g < MG; ++g)
+                        acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, __builtin_bit_cast(bf16x8_t, bcur[g]), acc[g], 0, 0, 0);
+                }
+                // the slot is dead now: request the tile of step s + RING into the same registers
+                ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
+                if (j + 1 < KC) {
+#pragma unroll
+                    for (int g = 0; g < MG; ++g) bcur[g] = bnxt[g];
                 }
             }
-        }
-    };
-
-    if (n_chunks > 0) {
-        load_x(0);
-        load_w(wcur, 0);
-        store_x(0, 0);
-        __syncthreads();
-        for (int ci = 0; ci < n_chunks; ci += 2) {
-            // even chunk: compute from wcur / buffer 0, prefetch into wnxt / buffer 1
-            if (ci + 1 < n_chunks) { load_x(ci + 1); load_w(wnxt, ci + 1); }
-            if (active) compute(wcur, ci, 0);
-            if (ci + 1 < n_chunks) store_x(ci + 1, 1);
-            __syncthreads();
-            if (ci + 1 >= n_chunks) break;
-            // odd chunk
-            if (ci + 2 < n_chunks) { load_x(ci + 2); load_w(wcur, ci + 2); }
-            if (active) compute(wnxt, ci + 1, 1);
-            if (ci + 2 < n_chunks) store_x(ci + 2, 0);
             __syncthreads();
         }
     }
-    if (!active) return;
+
+    // sum the k-slices of each n-tile in slice order (the activation buffers are free now)
+    if (WK > 1) {
+        float *red = (float *)&xs[0][0][0];
+        if (wk > 0 && active) {
+            float *dst = red + ((size_t)((wk - 1) * WN + wn) * MG * 16) * 64 + lane;
+#pragma unroll
+            for (int g = 0; g < MG; ++g)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dst[(g * 16 + r) * 64] = acc[g][r];
+        }
+        __syncthreads();
+        if (wk == 0 && active) {
+#pragma unroll
+            for (int w2 = 1; w2 < WK; ++w2) {
+                const float *src = red + ((size_t)((w2 - 1) * WN + wn) * MG * 16) * 64 + lane;
+#pragma unroll
+                for (int g = 0; g < MG; ++g)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[g][r] += src[(g * 16 + r) * 64];
+            }
+        }
+    }
+    if (!active || wk != 0) return;
 
     // accumulator register r of lane l: column m = 32*g + l%32, row n = 32*nt + 8*(r/4) + 4*(l/32) + r%4
     const int hl = lane >> 5, ml = lane & 31;
     if (EPI == HX_EPI_PARTIAL) {
-        float *y = a.y + blockIdx.y * a.split_stride;
+        float *y = a_y + blockIdx.y * a_split_stride;
 #pragma unroll
         for (int g = 0; g < MG; ++g) {
             const int m = 32 * g + ml;
-            if (m < a.M) {
+            if (m < a_M) {
 #pragma unroll
                 for (int j4 = 0; j4 < 4; ++j4) {
                     const int n = 32 * nt + 8 * j4 + 4 * hl;
-                    if (n < a.N)
-                        *(f32x4_t *)(y + (size_t)m * a.N + n) =
+                    if (n < a_N)
+                        *(f32x4_t *)(y + (size_t)m * a_N + n) =
                             f32x4_t{acc[g][4 * j4], acc[g][4 * j4 + 1], acc[g][4 * j4 + 2], acc[g][4 * j4 + 3]};
                 }
             }
@@ -166,7 +251,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int g = 0; g < MG; ++g) {
             const int m = 32 * g + ml;
-            if (m < a.M) {
+            if (m < a_M) {
 #pragma unroll
                 for (int j4 = 0; j4 < 2; ++j4) {
                     float v[4];
@@ -176,9 +261,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs a) {
                         v[i] = (gt / (1.0f + expf(-gt))) * up;
                     }
                     uint2 pk;
-                    pk.x = hx_pack_bf16x2(v[0], v[1]);
-                    pk.y = hx_pack_bf16x2(v[2], v[3]);
-                    *(uint2 *)(a.mp + hx_xp_index(m, 16 * nt + 8 * j4 + 4 * hl, MG)) = pk;
+                    pk.x = hx_cvt_pk_bf16(v[0], v[1]);
+                    pk.y = hx_cvt_pk_bf16(v[2], v[3]);
+                    *(uint2 *)(a_mp + hx_xp_index(m, 16 * nt + 8 * j4 + 4 * hl, MG)) = pk;
                 }
             }
         }
@@ -195,21 +280,39 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float v = acc[g][4 * j4 + i];
-                    if (n + i < a.N && v > best) { best = v; best_n = n + i; }
+                    if (n + i < a_N && v > best) { best = v; best_n = n + i; }
                 }
-                if (a.y != nullptr && m < a.M && n < a.N)
-                    *(f32x4_t *)(a.y + (size_t)m * a.N + n) =
+                if (a_y != nullptr && m < a_M && n < a_N)
+                    *(f32x4_t *)(a_y + (size_t)m * a_N + n) =
                         f32x4_t{acc[g][4 * j4], acc[g][4 * j4 + 1], acc[g][4 * j4 + 2], acc[g][4 * j4 + 3]};
             }
             const float ov = __shfl_xor(best, 32);
             const int on = __shfl_xor(best_n, 32);
             if (ov > best || (ov == best && on < best_n)) { best = ov; best_n = on; }
-            if (hl == 0 && m < a.M) {
-                a.amax_val[(size_t)m * a.n_tiles + nt] = best;
-                a.amax_idx[(size_t)m * a.n_tiles + nt] = best_n;
+            if (hl == 0 && m < a_M) {
+                a_amax_val[(size_t)m * a_n_tiles + nt] = best;
+                a_amax_idx[(size_t)m * a_n_tiles + nt] = best_n;
             }
         }
     }
+}
+
+#define HX_GEMM_ARGS a.wp, a.xp, a.k_steps, a.n_tiles, a.steps_per_split, a.steps_per_wave, a.M, a.N, a.y, a.split_stride, a.mp, a.amax_val, a.amax_idx
+template <int MG, int WN, int WK>
+static void launch_gemm_epi(int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
+    dim3 block(64 * (WN * WK + 1));
+    if (epilogue == HX_EPI_PARTIAL) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, WK, HX_EPI_PARTIAL>), grid, block, 0, st, HX_GEMM_ARGS);
+    else if (WK == 1 && epilogue == HX_EPI_SWIGLU) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, 1, HX_EPI_SWIGLU>), grid, block, 0, st, HX_GEMM_ARGS);
+    else if (WK == 1) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, 1, HX_EPI_LOGITS>), grid, block, 0, st, HX_GEMM_ARGS);
+}
+
+template <int MG>
+static int launch_gemm_mg(int wn, int wk, int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
+    if (wn == 4 && wk == 1) launch_gemm_epi<MG, 4, 1>(epilogue, grid, st, a);
+    else if (wn == 2 && wk == 2 && epilogue == HX_EPI_PARTIAL && MG <= 4) launch_gemm_epi<(MG <= 4 ? MG : 4), 2, 2>(epilogue, grid, st, a);
+    else if (wn == 1 && wk == 4 && epilogue == HX_EPI_PARTIAL && MG <= 4) launch_gemm_epi<(MG <= 4 ? MG : 4), 1, 4>(epilogue, grid, st, a);
+    else return hx_fail(HX_E_RANGE, "unsupported product shape wn=%d wk=%d epilogue=%d", wn, wk, epilogue);
+    return HX_OK;
 }
 
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue, float *y,
@@ -219,8 +322,13 @@ int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void
     a.xp = (const uint4 *)xp;
     a.k_steps = m->k_steps;
     a.n_tiles = m->n_tiles;
-    const int splits = (epilogue == HX_EPI_PARTIAL) ? m->splits : 1;
+    const int mg = hx_m_groups(batch);
+    const bool fused = epilogue != HX_EPI_PARTIAL;
+    const int splits = fused ? 1 : m->splits;
+    int wn = fused ? 4 : m->wn, wk = fused ? 1 : m->wk;
+    if (mg == 8) { wn = 4; wk = 1; }       // 8 m-groups leave no LDS for the k-slice reduction
     a.steps_per_split = (m->k_steps + splits - 1) / splits;
+    a.steps_per_wave = (a.steps_per_split + wk - 1) / wk;
     a.M = batch;
     a.N = m->N;
     a.y = y;
@@ -228,22 +336,16 @@ int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void
     a.mp = (uint16_t *)mp_out;
     a.amax_val = (float *)(e->ws + e->map.amax_val);
     a.amax_idx = (int32_t *)(e->ws + e->map.amax_idx);
-    dim3 grid((m->n_tiles + 3) / 4, splits), block(256);
-    const int mg = hx_m_groups(batch);
-#define HX_GEMM_CASE(MGV)                                                                                          \
-    case MGV:                                                                                                      \
-        if (epilogue == HX_EPI_PARTIAL) hipLaunchKernelGGL((gemm_stream_kernel<MGV, HX_EPI_PARTIAL>), grid, block, 0, st, a); \
-        else if (epilogue == HX_EPI_SWIGLU) hipLaunchKernelGGL((gemm_stream_kernel<MGV, HX_EPI_SWIGLU>), grid, block, 0, st, a); \
-        else hipLaunchKernelGGL((gemm_stream_kernel<MGV, HX_EPI_LOGITS>), grid, block, 0, st, a);                  \
-        break;
+    dim3 grid((m->n_tiles + wn - 1) / wn, splits);
+    int rc;
     switch (mg) {
-        HX_GEMM_CASE(1)
-        HX_GEMM_CASE(2)
-        HX_GEMM_CASE(4)
-        HX_GEMM_CASE(8)
+        case 1: rc = launch_gemm_mg<1>(wn, wk, epilogue, grid, st, a); break;
+        case 2: rc = launch_gemm_mg<2>(wn, wk, epilogue, grid, st, a); break;
+        case 4: rc = launch_gemm_mg<4>(wn, wk, epilogue, grid, st, a); break;
+        case 8: rc = launch_gemm_mg<8>(wn, wk, epilogue, grid, st, a); break;
         default: return hx_fail(HX_E_RANGE, "batch %d exceeds 256", batch);
     }
-#undef HX_GEMM_CASE
+    if (rc) return rc;
     HX_CHECK_LAUNCH("gemm_stream");
     return HX_OK;
 }

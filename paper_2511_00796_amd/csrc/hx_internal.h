@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
+#include <utility>
 
 #include "../../include/hexdecode.h"
 
@@ -64,6 +66,14 @@ __device__ __forceinline__ uint32_t hx_pack_bf16x2(float lo, float hi) {
     return (uint32_t)hx_f32_to_bf16(lo) | ((uint32_t)hx_f32_to_bf16(hi) << 16);
 }
 
+// two fp32 -> packed bf16 pair with the hardware conversion (round-to-nearest-even)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t hx_cvt_pk_bf16(float lo, float hi) {
+    f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // m-groups (of 32 rows) of the packed activation buffers for a batch: rounded up to 1, 2, 4 or 8 so that
 // producers and the matrix products agree on one layout per batch size
 __host__ __device__ __forceinline__ int hx_m_groups(int batch) {
@@ -91,7 +101,8 @@ struct hx_matrix {          // one packed weight matrix
     size_t offset;          // byte offset in the weight buffer
     int K, N;               // logical shape
     int k_steps, n_tiles;   // K / 16, ceil(N / 32) (gate|up: intermediate / 16)
-    int splits;             // K-splits used by the streaming product (1 when the epilogue is fused)
+    int splits;             // K-splits over workgroups (1 when the epilogue is fused); partials summed by the consumer
+    int wn, wk;             // wavefronts per workgroup: wn n-tiles x wk k-slices (summed in LDS)
 };
 
 struct hx_layer_map {
@@ -129,6 +140,8 @@ struct hx_engine {
     hx_matrix wlm;
     hx_ws_map map;
     float *attn_capture;    // device or NULL
+    uint32_t profile_mask;  // kernel classes bracketed by events
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> *profile_events;   // [HX_K_COUNT], host
 };
 
 struct hx_kv {
@@ -154,7 +167,8 @@ int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int ba
 int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
                          hipStream_t st);
 int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
-                        const int32_t *table, int max_blocks, float *attn_f32_out, hipStream_t st);
+                        const int32_t *table, int max_blocks, hipStream_t st);
+int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st);
 
 // gemm.hip
 int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *src, int64_t rows, int64_t cols,

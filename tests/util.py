@@ -26,3 +26,59 @@ def f32_to_bf16_bits_ref(x: np.ndarray) -> np.ndarray:
     up = u >> 16
     inc = (low > 0x8000) | ((low == 0x8000) & ((up & 1) == 1))
     return (up + inc).astype(np.uint16)
+
+
+class OracleRows:
+    """Runs the CPU oracle for a few sampled rows of a large workload, layer by layer, as the
+    workload builder produces each layer's tensors on the GPU (`tap` protocol of
+    paper_2511_00796_amd.workload.build).  Rows are independent in the decode step, so the sampled
+    rows' results are exactly what the full-batch oracle would give for them."""
+
+    def __init__(self, shape, rows, ctx, seq_start, tokens):
+        from concurrent.futures import ThreadPoolExecutor
+        self.shape, self.rows = shape, list(rows)
+        self.ctx, self.seq_start, self.tokens = ctx, seq_start, tokens
+        self.cfg1 = oracle.make_config(shape)
+        self.cfg1.n_layers = 1
+        self.pool = ThreadPoolExecutor(max_workers=min(len(self.rows), 16))
+        self.x = {}
+        self.attn = {r: [] for r in self.rows}
+        self.globals = None
+        self.layer_w = None
+        self.logits, self.next = {}, {}
+
+    def tap(self, kind, layer, t):
+        if kind == "globals":
+            self.globals = {k: synth.as_u16(v) for k, v in t.items()}
+            H = self.shape.hidden
+            for r in self.rows:
+                self.x[r] = bits_to_f32(self.globals["embed"][int(self.tokens[r])]).copy()
+        elif kind == "layer":
+            self.layer_w = {k: synth.as_u16(v) for k, v in t.items()}
+        elif kind == "kv":
+            w1 = oracle.Weights(self.globals, [self.layer_w])
+
+            def run(r):
+                c = int(self.ctx[r])
+                a = int(self.seq_start[r])
+                nblk = (c + 1 + 15) // 16
+                kv = oracle.PagedKV(self.cfg1, nblk, n_layers=1)
+                table = np.arange(nblk, dtype=np.int32)[None, :]
+                k = synth.as_u16(t["k"][a:a + c])
+                v = synth.as_u16(t["v"][a:a + c])
+                kv.fill(0, k, v, np.array([0, c], dtype=np.int32), table)
+                att = oracle.layer_step(self.cfg1, w1.layer(0), self.x[r], c, kv.k[0], kv.v[0], table[0], want_attn=True)
+                return r, att
+            for r, att in self.pool.map(run, self.rows):
+                self.attn[r].append(att)
+
+    def finish(self):
+        cfg = oracle.make_config(self.shape)
+        w = oracle.Weights(self.globals, [self.layer_w])      # only embed / gf / wlm are used by head()
+
+        def run(r):
+            return r, oracle.head(cfg, w, self.x[r])
+        for r, (lg, tok) in self.pool.map(run, self.rows):
+            self.logits[r], self.next[r] = lg, tok
+        self.pool.shutdown()
+        return self
