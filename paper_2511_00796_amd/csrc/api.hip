@@ -59,36 +59,11 @@ static int attention_chunk() {
     return c / 16 * 16;
 }
 
-// Shape of the streaming product for one matrix: wn x wk wavefronts per workgroup and `splits` K-splits
-// over workgroups.  Wide matrices (gate|up, LM head) take 4 n-tiles per workgroup and the whole K, so the
-// epilogue can be fused; narrow ones (q/k/v, output, down projection) need K-parallelism to occupy 256
-// compute units: 2 x 2 wavefronts plus enough splits for about two workgroups per compute unit, bounded
-// so that each k-slice keeps at least 16 k-steps.  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
-static void choose_product_shape(hx_matrix *m, bool fused_epilogue) {
-    m->wn = 4; m->wk = 1; m->splits = 1;
-    if (fused_epilogue) return;
-    m->wn = 2; m->wk = 2;
-    int wgs = (m->n_tiles + m->wn - 1) / m->wn;
-    int s = (384 + wgs - 1) / wgs;
-    int cap = m->k_steps / (16 * m->wk);
-    if (s > 8) s = 8;
-    if (s > cap) s = cap;
-    if (s < 1) s = 1;
-    m->splits = s;
-    const char *ov = getenv("HX_GEMM_SHAPE");
-    int a, b, c;
-    if (ov && sscanf(ov, "%d,%d,%d", &a, &b, &c) == 3 && ((a == 4 && b == 1) || (a == 2 && b == 2) || (a == 1 && b == 4)) &&
-        c >= 1 && c <= 8 && m->k_steps / (b * c) >= 1) {
-        m->wn = a; m->wk = b; m->splits = c;
-    }
-}
-
-static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up, bool fused_epilogue) {
+static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up) {
     m->K = K;
     m->N = gate_up ? 2 * N : N;
     m->k_steps = K / 16;
     m->n_tiles = gate_up ? N / 16 : (N + 31) / 32;
-    choose_product_shape(m, fused_epilogue);
     m->offset = *at;
     *at = align_up(*at + (size_t)m->n_tiles * m->k_steps * 1024);
 }
@@ -113,17 +88,17 @@ static size_t map_weights(hx_engine *e) {
     for (int l = 0; l < c->n_layers; ++l) {
         hx_layer_map tmp;
         hx_layer_map *lm = e->layers ? &e->layers[l] : &tmp;
-        init_matrix(&lm->wqkv, &at, c->hidden, e->qkv_dim, false, false);
-        init_matrix(&lm->wo, &at, e->q_dim, c->hidden, false, false);
-        init_matrix(&lm->wgu, &at, c->hidden, c->intermediate, true, true);
-        init_matrix(&lm->wd, &at, c->intermediate, c->hidden, false, false);
+        init_matrix(&lm->wqkv, &at, c->hidden, e->qkv_dim, false);
+        init_matrix(&lm->wo, &at, e->q_dim, c->hidden, false);
+        init_matrix(&lm->wgu, &at, c->hidden, c->intermediate, true);
+        init_matrix(&lm->wd, &at, c->intermediate, c->hidden, false);
         lm->g1 = at; at = align_up(at + (size_t)c->hidden * 2);
         lm->g2 = at; at = align_up(at + (size_t)c->hidden * 2);
         lm->bqkv = at; at = align_up(at + (size_t)e->qkv_dim * 2);
     }
     e->embed = at; at = align_up(at + (size_t)c->vocab * c->hidden * 2);
     e->gf = at; at = align_up(at + (size_t)c->hidden * 2);
-    init_matrix(&e->wlm, &at, c->hidden, c->vocab, false, true);
+    init_matrix(&e->wlm, &at, c->hidden, c->vocab, false);
     return at;
 }
 
@@ -138,7 +113,7 @@ static size_t map_workspace(hx_engine *e) {
     m->ap = take((size_t)(e->q_dim / 16) * MG * 1024);
     m->mp = take((size_t)(c->intermediate / 16) * MG * 1024);
     size_t wide = (size_t)(e->qkv_dim > c->hidden ? e->qkv_dim : c->hidden);
-    m->ypart = take(8 * B * wide * 4);
+    m->ypart = take((size_t)HX_MAX_SPLITS * B * wide * 4);
     m->qp = take(B * c->n_kv_heads * (size_t)(e->D / 32) * 1024 + 16 * (size_t)e->D * 2);   // + one K tile of slack: the attention
                                                                                           // kernel may read a whole K|V tile starting at any query
     m->cs = take(2 * B * (e->D / 2) * 4);
@@ -421,16 +396,16 @@ extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t
     for (int l = 0; l < c->n_layers; ++l) {
         const hx_layer_map *lm = &e->layers[l];
         HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st));
-        HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim,
+        HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, hx_gemm_splits(&lm->wqkv, batch), (size_t)batch * e->qkv_dim,
                                                  positions, block_table, max_blocks, st));
         HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
         HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st));
         HX_TIMED(HX_K_GEMM_O, hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st));
-        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, lm->g2, st));
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wo, batch), (size_t)batch * c->hidden, lm->g2, st));
         HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st));
         HX_TIMED(HX_K_GEMM_DOWN, hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st));
         const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
-        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, next_gain, st));
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wd, batch), (size_t)batch * c->hidden, next_gain, st));
     }
     HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st));
     HX_TIMED(HX_K_SETUP, hx_launch_argmax_final(e, batch, next_tokens_out, st));
@@ -513,11 +488,11 @@ extern "C" int hx_stage_linear(hx_engine *e, int kind, int layer, int32_t batch,
         case HX_T_WQKV:
             if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
             if ((rc = hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
-            return hx_launch_sum_partials(e, batch, ypart, lm->wqkv.splits, (size_t)batch * e->qkv_dim, e->qkv_dim, y_dev, st);
+            return hx_launch_sum_partials(e, batch, ypart, hx_gemm_splits(&lm->wqkv, batch), (size_t)batch * e->qkv_dim, e->qkv_dim, y_dev, st);
         case HX_T_WO:
             if ((rc = hx_launch_pack_x(e, batch, x_dev, e->q_dim, ws + e->map.ap, st))) return rc;
             if ((rc = hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
-            return hx_launch_sum_partials(e, batch, ypart, lm->wo.splits, (size_t)batch * c->hidden, c->hidden, y_dev, st);
+            return hx_launch_sum_partials(e, batch, ypart, hx_gemm_splits(&lm->wo, batch), (size_t)batch * c->hidden, c->hidden, y_dev, st);
         case HX_T_WG:
             if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
             if ((rc = hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st))) return rc;
@@ -525,7 +500,7 @@ extern "C" int hx_stage_linear(hx_engine *e, int kind, int layer, int32_t batch,
         case HX_T_WD:
             if ((rc = hx_launch_pack_x(e, batch, x_dev, c->intermediate, ws + e->map.mp, st))) return rc;
             if ((rc = hx_launch_gemm(e, &lm->wd, batch, ws + e->map.mp, HX_EPI_PARTIAL, ypart, nullptr, st))) return rc;
-            return hx_launch_sum_partials(e, batch, ypart, lm->wd.splits, (size_t)batch * c->hidden, c->hidden, y_dev, st);
+            return hx_launch_sum_partials(e, batch, ypart, hx_gemm_splits(&lm->wd, batch), (size_t)batch * c->hidden, c->hidden, y_dev, st);
         case HX_T_WLM:
             if ((rc = hx_launch_pack_x(e, batch, x_dev, c->hidden, ws + e->map.xp, st))) return rc;
             if ((rc = hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, y_dev, nullptr, st))) return rc;

@@ -211,9 +211,11 @@ __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict_
 }
 
 // ---- combine ---------------------------------------------------------------------------------------------
-// o = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of the sequence, in chunk order.
-// One thread per (sequence, query head, 8 consecutive d); writes the bf16-rounded result into the
-// packed activation buffer of the output projection and, if asked, the unrounded fp32 values.
+// o = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of the sequence.
+// One wavefront per (sequence, query head): lane = (phase 0..3, d8 0..15); phase p takes chunks p, p+4, ...
+// in order, then the four phases are summed by a fixed shuffle tree (deterministic).  Lanes of phase 0
+// write the bf16-rounded result into the packed activation buffer of the output projection and, if asked,
+// the unrounded fp32 values.  D = 64 uses lanes d8 < 8 only.
 template <int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, int n_kv, int G,
                                                            const int32_t *__restrict__ first_item,
@@ -221,30 +223,41 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
                                                            const float *__restrict__ part_o,
                                                            uint16_t *__restrict__ ap, int m_groups,
                                                            float *__restrict__ attn_f32) {
-    constexpr int TPH = D / 8;                       // threads per head
-    int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    int d8 = gid % TPH;
-    int bh = gid / TPH;
+    const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= batch * n_q) return;
-    int b = bh / n_q, h = bh % n_q;
-    int kvh = h / G, g = h % G;
-    int i0 = first_item[b], i1 = first_item[b + 1];
+    const int lane = threadIdx.x & 63, d8 = lane & 15, ph = lane >> 4;
+    const bool has_d = d8 < D / 8;
+    const int b = bh / n_q, h = bh % n_q;
+    const int kvh = h / G, g = h % G;
+    const int i0 = first_item[b], i1 = first_item[b + 1];
     float M = HX_NEG_BIG;
-    for (int it = i0; it < i1; ++it) M = fmaxf(M, part_ml[((size_t)it * n_kv + kvh) * 32 + g]);
+    for (int it = i0 + ph; it < i1; it += 4) M = fmaxf(M, part_ml[((size_t)it * n_kv + kvh) * 32 + g]);
+    M = fmaxf(M, __shfl_xor(M, 16));
+    M = fmaxf(M, __shfl_xor(M, 32));
     float den = 0.f;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    for (int it = i0; it < i1; ++it) {
-        size_t pi = (size_t)it * n_kv + kvh;
-        float w = exp2f(part_ml[pi * 32 + g] - M);
+    for (int it = i0 + ph; it < i1; it += 4) {
+        const size_t pi = (size_t)it * n_kv + kvh;
+        const float w = __builtin_amdgcn_exp2f(part_ml[pi * 32 + g] - M);
         den += w * part_ml[pi * 32 + 16 + g];
-        const float *po = part_o + (pi * G + g) * D + d8 * 8;
-        f32x4_t a = *(const f32x4_t *)po, c = *(const f32x4_t *)(po + 4);
-        acc[0] += w * a[0]; acc[1] += w * a[1]; acc[2] += w * a[2]; acc[3] += w * a[3];
-        acc[4] += w * c[0]; acc[5] += w * c[1]; acc[6] += w * c[2]; acc[7] += w * c[3];
+        if (has_d) {
+            const float *po = part_o + (pi * G + g) * D + d8 * 8;
+            const f32x4_t a = *(const f32x4_t *)po, c = *(const f32x4_t *)(po + 4);
+            acc[0] += w * a[0]; acc[1] += w * a[1]; acc[2] += w * a[2]; acc[3] += w * a[3];
+            acc[4] += w * c[0]; acc[5] += w * c[1]; acc[6] += w * c[2]; acc[7] += w * c[3];
+        }
     }
-    float inv = 1.0f / den;
+    den += __shfl_xor(den, 16);
+    den += __shfl_xor(den, 32);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        acc[j] += __shfl_xor(acc[j], 16);
+        acc[j] += __shfl_xor(acc[j], 32);
+    }
+    if (ph != 0 || !has_d) return;
+    const float inv = 1.0f / den;
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] *= inv;
     if (attn_f32) {
@@ -253,8 +266,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
         *(f32x4_t *)(dst + 4) = f32x4_t{acc[4], acc[5], acc[6], acc[7]};
     }
     uint4 pk;
-    pk.x = hx_pack_bf16x2(acc[0], acc[1]); pk.y = hx_pack_bf16x2(acc[2], acc[3]);
-    pk.z = hx_pack_bf16x2(acc[4], acc[5]); pk.w = hx_pack_bf16x2(acc[6], acc[7]);
+    pk.x = hx_cvt_pk_bf16(acc[0], acc[1]); pk.y = hx_cvt_pk_bf16(acc[2], acc[3]);
+    pk.z = hx_cvt_pk_bf16(acc[4], acc[5]); pk.w = hx_cvt_pk_bf16(acc[6], acc[7]);
     *(uint4 *)(ap + hx_xp_index(b, h * D + d8 * 8, m_groups)) = pk;
 }
 
@@ -282,8 +295,7 @@ int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStr
     char *ws = e->ws;
     const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
     const int m_groups = hx_m_groups(batch);
-    const int threads = batch * n_q * (e->D / 8);
-    dim3 cgrid((threads + 255) / 256), cblock(256);
+    dim3 cgrid((batch * n_q + 3) / 4), cblock(256);
 #define HX_COMB_ARGS                                                                                             \
     batch, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.first_item), (const float *)(ws + e->map.part_ml),     \
         (const float *)(ws + e->map.part_o), (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out

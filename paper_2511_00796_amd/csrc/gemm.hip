@@ -51,18 +51,21 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 }
 
 // ---- the streaming product ------------------------------------------------------------------------------------
-// Workgroup = WN x WK consumer wavefronts + 1 producer wavefront.  Consumers: WN adjacent n-tiles, each
-// split into WK k-slices that are summed in slice order through LDS at the end; every consumer keeps
-// RING weight loads (1 KiB each, non-temporal) in flight in a register ring and issues no other
-// vector-memory load, so the in-order load counter never makes it wait for anything but the tile it is
-// about to use.  The producer copies the activations of the next chunks (KC k-steps per k-slice) from
-// L2 into a three-stage LDS buffer; one workgroup barrier per chunk hands them over.
+// Workgroup = WN x WK consumer wavefronts + NP producer wavefronts, one workgroup per compute unit.
+// Consumers: WN adjacent n-tiles, each split into WK k-slices that are summed in slice order through LDS at
+// the end.  Every consumer keeps RING weight loads (1 KiB each, non-temporal) in flight in a register ring
+// and issues no other vector-memory load, so the in-order load counter never makes it wait for anything but
+// the tile it is about to use.  Producers copy the activations of the coming chunks (KC k-steps of every
+// k-slice, 32 KiB per stage) from L2 straight into a four-stage LDS buffer; one workgroup barrier per chunk
+// hands a stage over.  With up to 96 KiB of activations in flight per compute unit the copy keeps pace with
+// the weight stream at HBM speed.
 #define HX_GEMM_RING 16
+#define HX_GEMM_NBUF 4
 
 struct GemmArgs {
     const uint4 *wp;      // packed weights
     const uint4 *xp;      // packed activations
-    int k_steps, n_tiles, steps_per_split, steps_per_wave;
+    int k_steps, n_tiles, tile0, tile_end, steps_per_split, steps_per_wave;   // n_tiles: whole matrix; [tile0, tile_end): this launch
     int M, N;
     float *y;             // PARTIAL: [splits][M][N]; LOGITS: [M][N] or NULL
     size_t split_stride;  // elements between splits of y
@@ -79,29 +82,41 @@ __device__ __forceinline__ u32x4_t hx_stream_load(const uint4 *p) {   // read-on
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
 #define HX_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
+template <int MG, int WK> struct GemmGeom {
+    static constexpr int KC0 = 32 / (WK * MG);
+    static constexpr int KC = KC0 > 8 ? 8 : (KC0 < 1 ? 1 : KC0);   // k-steps per LDS chunk
+    static constexpr int SLICE_U4 = KC * MG * 64;                   // uint4 per k-slice per stage
+    static constexpr int PVT = WK * KC * MG;                        // 1-KiB copies per stage
+    static constexpr int NP = PVT > 16 ? 2 : 1;                     // producer wavefronts
+    static constexpr int PVP = PVT / NP;                            // copies per producer per stage
+    static constexpr int STAGE_BYTES = WK * SLICE_U4 * 16;
+};
+template <int MG, int WN, int WK> constexpr int gemm_lds_bytes() {
+    constexpr int stages = HX_GEMM_NBUF * GemmGeom<MG, WK>::STAGE_BYTES;
+    constexpr int red = (WK - 1) * WN * MG * 4096;
+    return stages > red ? stages : red;
+}
+
 template <int MG, int WN, int WK, int EPI>
-__global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
-    const uint4 *__restrict__ a_wp, const uint4 *__restrict__ a_xp, int a_k_steps, int a_n_tiles, int a_steps_per_split,
-    int a_steps_per_wave, int a_M, int a_N, float *__restrict__ a_y, size_t a_split_stride, uint16_t *__restrict__ a_mp,
-    float *__restrict__ a_amax_val, int32_t *__restrict__ a_amax_idx) {
-    constexpr int RING = HX_GEMM_RING;
-    constexpr int NBUF = 4;
-    constexpr int KCMG = 16 / WK;                                    // KiB of activations per k-slice buffer
-    constexpr int KC = (KCMG / MG) > 8 ? 8 : ((KCMG / MG) < 1 ? 1 : (KCMG / MG));   // k-steps per LDS chunk
-    constexpr int CPR = RING / KC;                                   // chunks per ring revolution
-    constexpr int SLICE_U4 = KC * MG * 64;
-    constexpr int PV = WK * KC * MG;                                 // 1-KiB copies per chunk (producer)
+__global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_stream_kernel(
+    const uint4 *__restrict__ a_wp, const uint4 *__restrict__ a_xp, int a_k_steps, int a_n_tiles, int a_tile0,
+    int a_tile_end, int a_steps_per_split, int a_steps_per_wave, int a_M, int a_N, float *__restrict__ a_y, size_t a_split_stride,
+    uint16_t *__restrict__ a_mp, float *__restrict__ a_amax_val, int32_t *__restrict__ a_amax_idx) {
+    using GG = GemmGeom<MG, WK>;
+    constexpr int RING = HX_GEMM_RING, NBUF = HX_GEMM_NBUF;
+    constexpr int KC = GG::KC, CPR = RING / KC, SLICE_U4 = GG::SLICE_U4, NC = WN * WK;
+    // with at most 8 wavefronts per workgroup each may use 256 registers: enough to read B operands ahead
+    constexpr bool PREFETCH_B = (NC + GG::NP <= 8) && MG <= 4;
     static_assert(RING % KC == 0, "ring must hold whole chunks");
-    static_assert(2 * PV <= 63, "two chunks of copies must fit the load counter");
-    static_assert((WK - 1) * WN * MG * 4 <= NBUF * WK * KC * MG, "reduction scratch must fit the activation buffers");
-    __shared__ u32x4_t xs[NBUF][WK][SLICE_U4];
+    static_assert(2 * GG::PVP <= 63, "two stages of copies must fit the load counter");
+    extern __shared__ u32x4_t xs[];                      // [NBUF][WK][SLICE_U4]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform, kept in a scalar register
-    const bool producer = wave == WN * WK;               // the last wavefront only stages activations
-    const int wn = wave % WN, wk = producer ? 0 : wave / WN;
-    const int nt = blockIdx.x * WN + wn;
-    const bool active = !producer && nt < a_n_tiles;
+    const bool producer = wave >= NC;                    // the last wavefronts only stage activations
+    const int wn = producer ? 0 : wave % WN, wk = producer ? 0 : wave / WN;
+    const int nt = a_tile0 + blockIdx.x * WN + wn;
+    const bool active = !producer && nt < a_tile_end;
     const int split0 = blockIdx.y * a_steps_per_split;
     const int split1 = min(a_k_steps, split0 + a_steps_per_split);
     // every wavefront of the grid runs the same number of chunks: whole ring revolutions.  Steps past the end
@@ -112,35 +127,36 @@ __global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
     if (producer) {
         // k-slice w of this workgroup covers k-steps [split0 + w*spw, min(split1, +spw)); chunk c of it is a
         // contiguous run of the packed activations, copied L2 -> LDS without passing through registers.
-        // Chunks c+1 .. c+3 are in flight or ready while the consumers work on chunk c.
+        // Virtual chunk v is real chunk max(v - CPR, 0): the consumers spend their first ring revolution
+        // multiplying zeros (ring not filled yet) with chunk 0, then fall into step with the real chunks.
+        // Stages v+1 .. v+3 are in flight or ready while the consumers work on stage v.
         const u32x4_t *xp4 = (const u32x4_t *)a_xp;
         const int last_u4 = a_k_steps * MG * 64 - 1;
-        // virtual chunk v is real chunk max(v - CPR, 0): the consumers spend their first ring revolution
-        // multiplying zeros (ring not filled yet) with chunk 0, then fall into step with the real chunks
+        const int pid = wave - NC;
         auto copy_chunk = [&](int v) {
             const int buf = v % NBUF;
             const int c = max(v - CPR, 0);
 #pragma unroll
-            for (int w = 0; w < WK; ++w) {
+            for (int f = 0; f < GG::PVP; ++f) {
+                const int ff = pid * GG::PVP + f;        // copy index in the stage: (k-slice, 1-KiB piece)
+                const int w = ff / (KC * MG), i = ff % (KC * MG);
                 const int kb = min(split1, split0 + w * a_steps_per_wave);
-                const int base = (kb + c * KC) * MG * 64 + lane;
-#pragma unroll
-                for (int i = 0; i < KC * MG; ++i)
-                    __builtin_amdgcn_global_load_lds(
-                        (const void __attribute__((address_space(1))) *)(xp4 + min(base + i * 64, last_u4)),
-                        (void __attribute__((address_space(3))) *)&xs[buf][w][i * 64], 16, 0, 0);
+                const int src = min((kb + c * KC) * MG * 64 + i * 64 + lane, last_u4);
+                __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(xp4 + src),
+                                                 (void __attribute__((address_space(3))) *)&xs[(buf * WK + w) * SLICE_U4 + i * 64],
+                                                 16, 0, 0);
             }
         };
         const int n_virtual = n_chunks + CPR;
         copy_chunk(0);
         copy_chunk(1);
         copy_chunk(2);
-        __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * PV));        // chunk 0 has landed
+        __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * GG::PVP));   // stage 0 has landed
         __syncthreads();
         for (int v = 0; v < n_virtual; ++v) {
             if (v + 3 < n_virtual) {
-                copy_chunk(v + 3);                            // into the buffer the consumers left at the last barrier
-                __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * PV)); // chunk v + 1 has landed
+                copy_chunk(v + 3);                            // into the stage the consumers left at the last barrier
+                __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * GG::PVP)); // stage v + 1 has landed
             } else {
                 __builtin_amdgcn_s_waitcnt(HX_VMCNT(0));      // nothing is in flight once the loop ends
             }
@@ -155,7 +171,7 @@ __global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
     const int n_valid = active ? max(0, ke - kb0) : 0;               // steps that are multiplied
     const int kb = min(kb0, a_k_steps - 1);
     const int last = max(0, min(a_k_steps, kb + a_steps_per_wave) - kb - 1);   // last step whose tile may be read
-    const uint4 *wrow = a_wp + ((size_t)(active ? nt : 0) * a_k_steps + kb) * 64 + lane;
+    const uint4 *wrow = a_wp + ((size_t)(active ? nt : a_tile0) * a_k_steps + kb) * 64 + lane;
 
     f32x16_t acc[MG];
 #pragma unroll
@@ -165,7 +181,7 @@ __global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
 
     // The ring starts as zeros and the loop starts one revolution early (c0 = -CPR): that revolution
     // multiplies zeros while it requests the first RING tiles; from then on step s multiplies the tile
-    // requested RING steps earlier and immediately requests the tile of step s + RING into the same slot.
+    // requested RING steps earlier and then requests the tile of step s + RING into the same slot.
     // There is no separate prologue, so the only loads outstanding at any wait are the ring's own, in order.
     u32x4_t ring[RING];
 #pragma unroll
@@ -176,38 +192,53 @@ __global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
 #pragma unroll
         for (int cc = 0; cc < CPR; ++cc) {
             const int c = c0 + cc;
-            const u32x4_t *xb = &xs[(c + CPR) % NBUF][wk][lane];
-            // B operands are read from LDS one k-step ahead of the multiplies that use them
-            u32x4_t bcur[MG], bnxt[MG];
+            const u32x4_t *xb = &xs[(((c + CPR) % NBUF) * WK + wk) * SLICE_U4 + lane];
+            if (PREFETCH_B) {
+                // B operands are read from LDS one k-step ahead of the multiplies that use them
+                u32x4_t bcur[MG], bnxt[MG];
 #pragma unroll
-            for (int g = 0; g < MG; ++g) bcur[g] = xb[g * 64];
+                for (int g = 0; g < MG; ++g) bcur[g] = xb[g * 64];
 #pragma unroll
-            for (int j = 0; j < KC; ++j) {
-                const int s = c * KC + j;
-                if (j + 1 < KC) {
+                for (int j = 0; j < KC; ++j) {
+                    const int s = c * KC + j;
+                    if (j + 1 < KC) {
 #pragma unroll
-                    for (int g = 0; g < MG; ++g) bnxt[g] = xb[((j + 1) * MG + g) * 64];
+                        for (int g = 0; g < MG; ++g) bnxt[g] = xb[((j + 1) * MG + g) * 64];
+                    }
+                    if (s < n_valid) {
+                        const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
+#pragma unroll
+                        for (int g = 0; g < MG; ++g)
+                            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, __builtin_bit_cast(bf16x8_t, bcur[g]), acc[g], 0, 0, 0);
+                    }
+                    // the slot is dead now: request the tile of step s + RING into the same registers
+                    ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
+                    if (j + 1 < KC) {
+#pragma unroll
+                        for (int g = 0; g < MG; ++g) bcur[g] = bnxt[g];
+                    }
                 }
-                if (s < n_valid) {
-                    const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
+            } else {
 #pragma unroll
-                    for (int g = 0; g < MG; ++g)
-                        acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, __builtin_bit_cast(bf16x8_t, bcur[g]), acc[g], 0, 0, 0);
-                }
-                // the slot is dead now: request the tile of step s + RING into the same registers
-                ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
-                if (j + 1 < KC) {
+                for (int j = 0; j < KC; ++j) {
+                    const int s = c * KC + j;
+                    if (s < n_valid) {
+                        const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
 #pragma unroll
-                    for (int g = 0; g < MG; ++g) bcur[g] = bnxt[g];
+                        for (int g = 0; g < MG; ++g)
+                            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                aop, __builtin_bit_cast(bf16x8_t, xb[(j * MG + g) * 64]), acc[g], 0, 0, 0);
+                    }
+                    ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
                 }
             }
             __syncthreads();
         }
     }
 
-    // sum the k-slices of each n-tile in slice order (the activation buffers are free now)
+    // sum the k-slices of each n-tile in slice order (the activation stages are free now)
     if (WK > 1) {
-        float *red = (float *)&xs[0][0][0];
+        float *red = (float *)xs;
         if (wk > 0 && active) {
             float *dst = red + ((size_t)((wk - 1) * WN + wn) * MG * 16) * 64 + lane;
 #pragma unroll
@@ -297,56 +328,116 @@ __global__ __launch_bounds__(64 * (WN * WK + 1)) void gemm_stream_kernel(
     }
 }
 
-#define HX_GEMM_ARGS a.wp, a.xp, a.k_steps, a.n_tiles, a.steps_per_split, a.steps_per_wave, a.M, a.N, a.y, a.split_stride, a.mp, a.amax_val, a.amax_idx
+// ---- host side: one launch of a given shape -----------------------------------------------------------------------
+#define HX_GEMM_ARGS a.wp, a.xp, a.k_steps, a.n_tiles, a.tile0, a.tile_end, a.steps_per_split, a.steps_per_wave, a.M, a.N, a.y, \
+                     a.split_stride, a.mp, a.amax_val, a.amax_idx
+
+template <int MG, int WN, int WK, int EPI>
+static int launch_one(dim3 grid, hipStream_t st, const GemmArgs &a) {
+    constexpr int lds = gemm_lds_bytes<MG, WN, WK>();
+    static bool configured = false;                      // the opt-in for more than 64 KiB of LDS is per kernel
+    if (!configured) {
+        HX_CHECK_HIP(hipFuncSetAttribute((const void *)gemm_stream_kernel<MG, WN, WK, EPI>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        configured = true;
+    }
+    dim3 block(64 * (WN * WK + GemmGeom<MG, WK>::NP));
+    hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, WK, EPI>), grid, block, lds, st, HX_GEMM_ARGS);
+    return HX_OK;
+}
+
 template <int MG, int WN, int WK>
-static void launch_gemm_epi(int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
-    dim3 block(64 * (WN * WK + 1));
-    if (epilogue == HX_EPI_PARTIAL) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, WK, HX_EPI_PARTIAL>), grid, block, 0, st, HX_GEMM_ARGS);
-    else if (WK == 1 && epilogue == HX_EPI_SWIGLU) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, 1, HX_EPI_SWIGLU>), grid, block, 0, st, HX_GEMM_ARGS);
-    else if (WK == 1) hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, 1, HX_EPI_LOGITS>), grid, block, 0, st, HX_GEMM_ARGS);
+static int launch_epi(int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
+    if (epilogue == HX_EPI_PARTIAL) return launch_one<MG, WN, WK, HX_EPI_PARTIAL>(grid, st, a);
+    if (epilogue == HX_EPI_SWIGLU) return launch_one<MG, WN, WK, HX_EPI_SWIGLU>(grid, st, a);
+    return launch_one<MG, WN, WK, HX_EPI_LOGITS>(grid, st, a);
 }
 
 template <int MG>
-static int launch_gemm_mg(int wn, int wk, int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
-    if (wn == 4 && wk == 1) launch_gemm_epi<MG, 4, 1>(epilogue, grid, st, a);
-    else if (wn == 2 && wk == 2 && epilogue == HX_EPI_PARTIAL && MG <= 4) launch_gemm_epi<(MG <= 4 ? MG : 4), 2, 2>(epilogue, grid, st, a);
-    else if (wn == 1 && wk == 4 && epilogue == HX_EPI_PARTIAL && MG <= 4) launch_gemm_epi<(MG <= 4 ? MG : 4), 1, 4>(epilogue, grid, st, a);
-    else return hx_fail(HX_E_RANGE, "unsupported product shape wn=%d wk=%d epilogue=%d", wn, wk, epilogue);
-    return HX_OK;
+static int launch_shape(int wn, int wk, int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
+    if (wn == 4 && wk == 2) return launch_epi<MG, 4, 2>(epilogue, grid, st, a);
+    if (wn == 4 && wk == 1) return launch_epi<MG, 4, 1>(epilogue, grid, st, a);
+    if (MG <= 4) {      // 8 m-groups leave no LDS for the reduction of more than two k-slices
+        if (wn == 2 && wk == 4) return launch_epi<(MG <= 4 ? MG : 4), 2, 4>(epilogue, grid, st, a);
+        if (wn == 1 && wk == 8) return launch_epi<(MG <= 4 ? MG : 4), 1, 8>(epilogue, grid, st, a);
+    }
+    return hx_fail(HX_E_RANGE, "unsupported product shape wn=%d wk=%d for %d m-groups", wn, wk, MG);
+}
+
+// ---- host side: how to cut one product into launches ---------------------------------------------------------------
+// A workgroup occupies a whole compute unit (128 KiB of LDS), so a launch runs in rounds of HX_CUS
+// workgroups.  Measured on MI355X the 4 x 1 shape (four n-tiles sharing one activation stream, 32 KiB
+// stages, a barrier every 8 k-steps) is the fastest; products with a fused epilogue run it over the whole
+// K, products whose consumer kernel sums split partials are cut along K into as many splits (at most
+// HX_MAX_SPLITS, at least 16 k-steps each) as it takes to give every compute unit a workgroup.
+// HX_GEMM_SHAPE="wn,wk,splits" overrides the choice for the split products (tuning).
+#define HX_CUS 256
+
+struct gemm_launch { int wn, wk, splits, tile0, tiles; };
+
+static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_launch *out) {
+    gemm_launch l{4, 1, 1, 0, n_tiles};
+    if (partial) {
+        const int groups = (n_tiles + 3) / 4;
+        int s = (HX_CUS + groups / 2) / groups;
+        const int cap = k_steps / 16;
+        if (s > HX_MAX_SPLITS) s = HX_MAX_SPLITS;
+        if (s > cap) s = cap;
+        if (s < 1) s = 1;
+        l.splits = s;
+        int a, b, c;
+        const char *ov = getenv("HX_GEMM_SHAPE");
+        if (ov && sscanf(ov, "%d,%d,%d", &a, &b, &c) == 3 && c >= 1 && c <= HX_MAX_SPLITS && k_steps / (b * c) >= 1 &&
+            ((a == 4 && (b == 1 || b == 2)) || (mg <= 4 && ((a == 2 && b == 4) || (a == 1 && b == 8))))) {
+            l.wn = a; l.wk = b; l.splits = c;
+        }
+    }
+    out[0] = l;
+    return 1;
+}
+
+int hx_gemm_splits(const hx_matrix *m, int batch) {
+    gemm_launch plan[2];
+    plan_product(m->n_tiles, m->k_steps, hx_m_groups(batch), true, plan);
+    return plan[0].splits;
 }
 
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue, float *y,
                    void *mp_out, hipStream_t st) {
-    GemmArgs a;
-    a.wp = (const uint4 *)(e->weights + m->offset);
-    a.xp = (const uint4 *)xp;
-    a.k_steps = m->k_steps;
-    a.n_tiles = m->n_tiles;
     const int mg = hx_m_groups(batch);
-    const bool fused = epilogue != HX_EPI_PARTIAL;
-    const int splits = fused ? 1 : m->splits;
-    int wn = fused ? 4 : m->wn, wk = fused ? 1 : m->wk;
-    if (mg == 8) { wn = 4; wk = 1; }       // 8 m-groups leave no LDS for the k-slice reduction
-    a.steps_per_split = (m->k_steps + splits - 1) / splits;
-    a.steps_per_wave = (a.steps_per_split + wk - 1) / wk;
-    a.M = batch;
-    a.N = m->N;
-    a.y = y;
-    a.split_stride = (size_t)batch * m->N;
-    a.mp = (uint16_t *)mp_out;
-    a.amax_val = (float *)(e->ws + e->map.amax_val);
-    a.amax_idx = (int32_t *)(e->ws + e->map.amax_idx);
-    dim3 grid((m->n_tiles + wn - 1) / wn, splits);
-    int rc;
-    switch (mg) {
-        case 1: rc = launch_gemm_mg<1>(wn, wk, epilogue, grid, st, a); break;
-        case 2: rc = launch_gemm_mg<2>(wn, wk, epilogue, grid, st, a); break;
-        case 4: rc = launch_gemm_mg<4>(wn, wk, epilogue, grid, st, a); break;
-        case 8: rc = launch_gemm_mg<8>(wn, wk, epilogue, grid, st, a); break;
-        default: return hx_fail(HX_E_RANGE, "batch %d exceeds 256", batch);
+    const bool partial = epilogue == HX_EPI_PARTIAL;
+    gemm_launch plan[2];
+    const int n_launch = plan_product(m->n_tiles, m->k_steps, mg, partial, plan);
+    for (int li = 0; li < n_launch; ++li) {
+        const gemm_launch &pl = plan[li];
+        GemmArgs a;
+        a.wp = (const uint4 *)(e->weights + m->offset);
+        a.xp = (const uint4 *)xp;
+        a.k_steps = m->k_steps;
+        a.n_tiles = m->n_tiles;
+        a.tile0 = pl.tile0;
+        a.tile_end = pl.tile0 + pl.tiles;
+        a.steps_per_split = (m->k_steps + pl.splits - 1) / pl.splits;
+        a.steps_per_wave = (a.steps_per_split + pl.wk - 1) / pl.wk;
+        a.M = batch;
+        a.N = m->N;
+        a.y = y;
+        a.split_stride = (size_t)batch * m->N;
+        a.mp = (uint16_t *)mp_out;
+        a.amax_val = (float *)(e->ws + e->map.amax_val);
+        a.amax_idx = (int32_t *)(e->ws + e->map.amax_idx);
+        dim3 grid((pl.tiles + pl.wn - 1) / pl.wn, pl.splits);
+        int rc;
+        switch (mg) {
+            case 1: rc = launch_shape<1>(pl.wn, pl.wk, epilogue, grid, st, a); break;
+            case 2: rc = launch_shape<2>(pl.wn, pl.wk, epilogue, grid, st, a); break;
+            case 4: rc = launch_shape<4>(pl.wn, pl.wk, epilogue, grid, st, a); break;
+            case 8: rc = launch_shape<8>(pl.wn, pl.wk, epilogue, grid, st, a); break;
+            default: return hx_fail(HX_E_RANGE, "batch %d exceeds 256", batch);
+        }
+        if (rc) return rc;
+        HX_CHECK_LAUNCH("gemm_stream");
     }
-    if (rc) return rc;
-    HX_CHECK_LAUNCH("gemm_stream");
     return HX_OK;
 }
 

@@ -39,6 +39,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define HX_WAVE 64
 #define HX_BLOCK_TOKENS 16
 #define HX_MAX_HIDDEN 8192
+#define HX_MAX_SPLITS 9       // K-splits of a product whose partials are summed by its consumer kernel
 
 // ---- error reporting (api.hip) -------------------------------------------------------------------
 int hx_fail(int code, const char *fmt, ...);
@@ -101,8 +102,6 @@ struct hx_matrix {          // one packed weight matrix
     size_t offset;          // byte offset in the weight buffer
     int K, N;               // logical shape
     int k_steps, n_tiles;   // K / 16, ceil(N / 32) (gate|up: intermediate / 16)
-    int splits;             // K-splits over workgroups (1 when the epilogue is fused); partials summed by the consumer
-    int wn, wk;             // wavefronts per workgroup: wn n-tiles x wk k-slices (summed in LDS)
 };
 
 struct hx_layer_map {
@@ -176,6 +175,7 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 enum { HX_EPI_PARTIAL = 0, HX_EPI_SWIGLU = 1, HX_EPI_LOGITS = 2 };
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue,
                    float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st);
+int hx_gemm_splits(const hx_matrix *m, int batch);   // K-splits the planner uses for a product with split partials
 int hx_launch_argmax_final(const hx_engine *e, int batch, int32_t *tokens_out, hipStream_t st);
 
 // elementwise.hip

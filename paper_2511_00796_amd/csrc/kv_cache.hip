@@ -72,12 +72,16 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
 }
 
 // ---- bias + RoPE + append -------------------------------------------------------------------------------
-// grid = batch, 256 threads.  The q/k/v projection arrives as `splits` fp32 partial results
-// [split][batch][qkv_dim] (summed here in split order), the bias is added, q and k heads are rotated
-// by the position's angles (pairs (i, i + D/2)), q is written as the packed bf16 B operand of the
-// attention kernel, k and v are rounded to bf16 and stored at (block_table[b][pos/16], pos%16).
+// The q/k/v projection arrives as `splits` fp32 partial results [split][batch][qkv_dim] (summed here in
+// split order), the bias is added, q and k heads are rotated by the position's angles (pairs (i, i + D/2)),
+// q is written as the packed bf16 B operand of the attention kernel, k and v are rounded to bf16 and stored
+// at (block_table[b][pos/16], pos%16).
+// One thread per work item of 16 values: for q and k heads, 8 consecutive d of the lower half and the 8
+// matching d of the upper half (both ends of the rotation, two 16-byte stores); for v, 16 consecutive d.
+// grid (batch, ceil(items / 128)), 128 threads.  Query rows g >= G of the packed operand are never written:
+// they only feed accumulator columns that nobody reads.
 template <int D>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ ypart, int splits,
+__global__ __launch_bounds__(128) void rope_append_kernel(const float *__restrict__ ypart, int splits,
                                                           size_t split_stride, const uint16_t *__restrict__ bias,
                                                           int has_bias, const float *__restrict__ cs,
                                                           const int32_t *__restrict__ positions,
@@ -86,55 +90,75 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           uint16_t *__restrict__ qp, int n_q, int n_kv, int G,
                                                           int max_batch) {
     constexpr int HALF = D / 2;
+    constexpr int RPH = HALF / 8;                         // rotation items per head
     const int b = blockIdx.x;
+    const int item = blockIdx.y * blockDim.x + threadIdx.x;
+    const int rot_items = (n_q + n_kv) * RPH;
+    const int v_items = n_kv * (D / 16);
+    if (item >= rot_items + v_items) return;
     const int qkv_dim = (n_q + 2 * n_kv) * D;
-    const float *cosv = cs + (size_t)b * HALF;
-    const float *sinv = cs + (size_t)max_batch * HALF + (size_t)b * HALF;
     const int pos = positions[b];
     const int32_t blk = table[(size_t)b * max_blocks + (pos >> 4)];
     const int slot = pos & 15;
 
-    auto value = [&](int col) -> float {
-        float s = 0.f;
-        for (int sp = 0; sp < splits; ++sp) s += ypart[sp * split_stride + (size_t)b * qkv_dim + col];
-        if (has_bias) s += hx_bf16_to_f32(bias[col]);
-        return s;
+    auto gather8 = [&](int col, float *out) {            // sum of the split partials + bias, 8 consecutive columns
+#pragma unroll
+        for (int j = 0; j < 8; ++j) out[j] = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            const float *src = ypart + sp * split_stride + (size_t)b * qkv_dim + col;
+            const f32x4_t a = *(const f32x4_t *)src, c = *(const f32x4_t *)(src + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { out[j] += a[j]; out[4 + j] += c[j]; }
+        }
+        if (has_bias) {
+            const uint4 raw = *(const uint4 *)(bias + col);
+            const uint16_t *b16 = (const uint16_t *)&raw;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) out[j] += hx_bf16_to_f32(b16[j]);
+        }
+    };
+    auto pack8 = [](const float *v) {
+        uint4 pk;
+        pk.x = hx_cvt_pk_bf16(v[0], v[1]); pk.y = hx_cvt_pk_bf16(v[2], v[3]);
+        pk.z = hx_cvt_pk_bf16(v[4], v[5]); pk.w = hx_cvt_pk_bf16(v[6], v[7]);
+        return pk;
     };
 
-    // rotated heads: q heads then k heads, one thread per pair (i, i + HALF)
-    const int rot_pairs = (n_q + n_kv) * HALF;
-    for (int idx = threadIdx.x; idx < rot_pairs; idx += blockDim.x) {
-        int head = idx / HALF, i = idx % HALF;
-        float a = value(head * D + i), c2 = value(head * D + i + HALF);
-        float c = cosv[i], s = sinv[i];
-        float r0 = a * c - c2 * s, r1 = c2 * c + a * s;
-        if (head < n_q) {
-            int kvh = head / G, g = head % G;
-            uint16_t *dst = qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512;
-            int d0 = i, d1 = i + HALF;
-            dst[(d0 >> 5) * 512 + ((((d0 >> 3) & 3) * 16 + g) << 3) + (d0 & 7)] = hx_f32_to_bf16(r0);
-            dst[(d1 >> 5) * 512 + ((((d1 >> 3) & 3) * 16 + g) << 3) + (d1 & 7)] = hx_f32_to_bf16(r1);
-        } else {
-            int kvh = head - n_q;
-            uint16_t *ktile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes);
-            ktile[hx_ktile_index(slot, i)] = hx_f32_to_bf16(r0);
-            ktile[hx_ktile_index(slot, i + HALF)] = hx_f32_to_bf16(r1);
+    if (item < rot_items) {
+        const int head = item / RPH, i0 = (item % RPH) * 8;
+        float lo[8], hi[8], r0[8], r1[8];
+        gather8(head * D + i0, lo);
+        gather8(head * D + HALF + i0, hi);
+        const float *cosv = cs + (size_t)b * HALF + i0;
+        const float *sinv = cs + (size_t)max_batch * HALF + (size_t)b * HALF + i0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float c = cosv[j], sn = sinv[j];
+            r0[j] = lo[j] * c - hi[j] * sn;
+            r1[j] = hi[j] * c + lo[j] * sn;
         }
-    }
-    // v heads: plain rounding
-    for (int idx = threadIdx.x; idx < n_kv * D; idx += blockDim.x) {
-        int kvh = idx / D, d = idx % D;
-        uint16_t *vtile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes + tile_bytes);
-        vtile[hx_vtile_index(slot, d)] = hx_f32_to_bf16(value((n_q + n_kv) * D + idx));
-    }
-    // unused query rows g >= G of every packed operand are zero
-    if (G < 16) {
-        const int zero_per_kvh = (16 - G) * D;
-        for (int idx = threadIdx.x; idx < n_kv * zero_per_kvh; idx += blockDim.x) {
-            int kvh = idx / zero_per_kvh, r = idx % zero_per_kvh;
-            int g = G + r / D, d = r % D;
+        if (head < n_q) {
+            const int kvh = head / G, g = head % G;
             uint16_t *dst = qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512;
-            dst[(d >> 5) * 512 + ((((d >> 3) & 3) * 16 + g) << 3) + (d & 7)] = 0;
+            const int d0 = i0, d1 = i0 + HALF;
+            *(uint4 *)(dst + (d0 >> 5) * 512 + ((((d0 >> 3) & 3) * 16 + g) << 3)) = pack8(r0);
+            *(uint4 *)(dst + (d1 >> 5) * 512 + ((((d1 >> 3) & 3) * 16 + g) << 3)) = pack8(r1);
+        } else {
+            const int kvh = head - n_q;
+            uint16_t *ktile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes);
+            *(uint4 *)(ktile + hx_ktile_index(slot, i0)) = pack8(r0);
+            *(uint4 *)(ktile + hx_ktile_index(slot, i0 + HALF)) = pack8(r1);
+        }
+    } else {
+        const int vi = item - rot_items;
+        const int kvh = vi / (D / 16), d0 = (vi % (D / 16)) * 16;
+        uint16_t *vtile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes + tile_bytes);
+        float v[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            gather8((n_q + n_kv) * D + kvh * D + d0 + 8 * h, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vtile[hx_vtile_index(slot, d0 + 8 * h + j)] = hx_f32_to_bf16(v[j]);
         }
     }
 }
@@ -147,7 +171,8 @@ int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int ba
     const uint16_t *bias = (const uint16_t *)(e->weights + lm.bqkv);
     const float *cs = (const float *)(e->ws + e->map.cs);
     uint16_t *qp = (uint16_t *)(e->ws + e->map.qp);
-    dim3 grid(batch), block(256);
+    const int items = (e->cfg.n_q_heads + e->cfg.n_kv_heads) * (e->D / 16) + e->cfg.n_kv_heads * (e->D / 16);
+    dim3 grid(batch, (items + 127) / 128), block(128);
     if (e->D == 128)
         hipLaunchKernelGGL((rope_append_kernel<128>), grid, block, 0, st, ypart, splits, split_stride, bias,
                            e->cfg.qkv_bias, cs, positions, table, max_blocks, pool_layer, kv->block_bytes,
