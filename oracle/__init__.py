@@ -16,27 +16,32 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "decode_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+_LIB_DESC = os.path.join(_HERE, "liboracle_desc.so")
 
 # plain IEEE arithmetic: no fast-math, no fused multiply-add contraction
 _CFLAGS = ["-O2", "-ftree-vectorize", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11"]
 
 
-def build(force: bool = True) -> str:
+def build(force: bool = True, descending: bool = False) -> str:
     """Compile the oracle with gcc.  AVX2 is used when this CPU has it (it only widens the
-    loops that run over independent outputs; every sum keeps its ascending order)."""
-    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
-        return _LIB
+    loops that run over independent outputs; every sum keeps its order).  ``descending`` builds the
+    sensitivity variant whose matrix products add their terms in descending k."""
+    out = _LIB_DESC if descending else _LIB
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+        return out
     flags = list(_CFLAGS)
+    if descending:
+        flags.append("-DORC_SUM_DESCENDING")
     try:
         with open("/proc/cpuinfo") as f:
             if " avx2 " in f.read():
                 flags.append("-mavx2")
     except OSError:
         pass
-    tmp = _LIB + ".tmp.%d" % os.getpid()
+    tmp = out + ".tmp.%d" % os.getpid()
     subprocess.run(["gcc", *flags, _SRC, "-o", tmp, "-lm"], check=True)
-    os.replace(tmp, _LIB)
-    return _LIB
+    os.replace(tmp, out)
+    return out
 
 
 class _Config(C.Structure):
@@ -54,25 +59,50 @@ class _Weights(C.Structure):
 
 
 _lib = None
+_lib_desc = None
+_use_desc = False
+
+
+class descending_sums:
+    """Context manager: inside it every oracle call runs the variant built with
+    -DORC_SUM_DESCENDING (same arithmetic, matrix-product terms added in the opposite order)."""
+
+    def __enter__(self):
+        global _use_desc
+        self._prev = _use_desc
+        _use_desc = True
+        return self
+
+    def __exit__(self, *exc):
+        global _use_desc
+        _use_desc = self._prev
+        return False
+
+
+def _load(path):
+    L = C.CDLL(path)
+    L.orc_bf16_to_f32.restype = C.c_float
+    L.orc_bf16_to_f32.argtypes = [C.c_uint16]
+    L.orc_f32_to_bf16.restype = C.c_uint16
+    L.orc_f32_to_bf16.argtypes = [C.c_float]
+    L.orc_silu.restype = C.c_float
+    L.orc_silu.argtypes = [C.c_float]
+    L.orc_argmax.restype = C.c_int32
+    L.orc_head.restype = C.c_int32
+    L.orc_decode_step.restype = C.c_int
+    L.orc_num_threads.restype = C.c_int
+    return L
 
 
 def lib():
     """The loaded shared object (built on first use when absent or older than its source)."""
-    global _lib
+    global _lib, _lib_desc
+    if _use_desc:
+        if _lib_desc is None:
+            _lib_desc = _load(build(force=False, descending=True))
+        return _lib_desc
     if _lib is None:
-        build(force=False)
-        L = C.CDLL(_LIB)
-        L.orc_bf16_to_f32.restype = C.c_float
-        L.orc_bf16_to_f32.argtypes = [C.c_uint16]
-        L.orc_f32_to_bf16.restype = C.c_uint16
-        L.orc_f32_to_bf16.argtypes = [C.c_float]
-        L.orc_silu.restype = C.c_float
-        L.orc_silu.argtypes = [C.c_float]
-        L.orc_argmax.restype = C.c_int32
-        L.orc_head.restype = C.c_int32
-        L.orc_decode_step.restype = C.c_int
-        L.orc_num_threads.restype = C.c_int
-        _lib = L
+        _lib = _load(build(force=False))
     return _lib
 
 

@@ -17,7 +17,9 @@
  *
  * Nothing here is blocked, fused, tiled or reordered.  It shares no code, table or header
  * with the GPU library.  Only tests, the smoke check and the benchmark's CPU-baseline leg call
- * it.  Parity status: every function is pinned by tests/test_oracle_*.py against closed
+ * it.  Built with -DORC_SUM_DESCENDING the matrix products add their terms in descending k: an
+ * equally valid fp32 evaluation used only to measure how far two correct implementations drift apart.
+ * Parity status: every function is pinned by tests/test_oracle_*.py against closed
  * forms, invariants, numpy / torch library routines and brute-force recomputation; the paper
  * prints no worked numbers for this stage, so there is no golden value from it.
  */
@@ -80,7 +82,11 @@ void orc_rmsnorm(const float *x, const uint16_t *g, int n, float eps, float *y) 
 /* y[n] = sum_k x[k] * W[k][n] (+ bias[n]);  W is [K, N] row-major bf16, k ascending */
 void orc_linear(const float *x, const uint16_t *W, const uint16_t *bias, int K, int N, float *y) {
     for (int n = 0; n < N; ++n) y[n] = 0.0f;
+#ifdef ORC_SUM_DESCENDING /* sensitivity variant: the same sums in the opposite order (see tests) */
+    for (int k = K - 1; k >= 0; --k) {
+#else
     for (int k = 0; k < K; ++k) {
+#endif
         const float xk = x[k];
         const uint16_t *w = W + (size_t)k * N;
         for (int n = 0; n < N; ++n) y[n] += xk * orc_bf16_to_f32(w[n]);

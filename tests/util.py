@@ -34,9 +34,10 @@ class OracleRows:
     paper_2511_00796_amd.workload.build).  Rows are independent in the decode step, so the sampled
     rows' results are exactly what the full-batch oracle would give for them."""
 
-    def __init__(self, shape, rows, ctx, seq_start, tokens):
+    def __init__(self, shape, rows, ctx, seq_start, tokens, descending=False):
         from concurrent.futures import ThreadPoolExecutor
         self.shape, self.rows = shape, list(rows)
+        self.descending = descending          # run the equally valid descending-k variant of the oracle
         self.ctx, self.seq_start, self.tokens = ctx, seq_start, tokens
         self.cfg1 = oracle.make_config(shape)
         self.cfg1.n_layers = 1
@@ -48,6 +49,12 @@ class OracleRows:
         self.logits, self.next = {}, {}
 
     def tap(self, kind, layer, t):
+        if self.descending:
+            with oracle.descending_sums():
+                return self._tap(kind, layer, t)
+        return self._tap(kind, layer, t)
+
+    def _tap(self, kind, layer, t):
         if kind == "globals":
             self.globals = {k: synth.as_u16(v) for k, v in t.items()}
             H = self.shape.hidden
@@ -73,6 +80,12 @@ class OracleRows:
                 self.attn[r].append(att)
 
     def finish(self):
+        if self.descending:
+            with oracle.descending_sums():
+                return self._finish()
+        return self._finish()
+
+    def _finish(self):
         cfg = oracle.make_config(self.shape)
         w = oracle.Weights(self.globals, [self.layer_w])      # only embed / gf / wlm are used by head()
 
