@@ -355,44 +355,52 @@ static int launch_epi(int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a
 
 template <int MG>
 static int launch_shape(int wn, int wk, int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
-    if (wn == 4 && wk == 2) return launch_epi<MG, 4, 2>(epilogue, grid, st, a);
-    if (wn == 4 && wk == 1) return launch_epi<MG, 4, 1>(epilogue, grid, st, a);
-    if (MG <= 4) {      // 8 m-groups leave no LDS for the reduction of more than two k-slices
-        if (wn == 2 && wk == 4) return launch_epi<(MG <= 4 ? MG : 4), 2, 4>(epilogue, grid, st, a);
-        if (wn == 1 && wk == 8) return launch_epi<(MG <= 4 ? MG : 4), 1, 8>(epilogue, grid, st, a);
+    if (wk == 1) {
+        if (wn == 4) return launch_epi<MG, 4, 1>(epilogue, grid, st, a);
+        if (wn == 5) return launch_epi<MG, 5, 1>(epilogue, grid, st, a);
+        if (wn == 6) return launch_epi<MG, 6, 1>(epilogue, grid, st, a);
     }
+    if (wn == 4 && wk == 2) return launch_epi<MG, 4, 2>(epilogue, grid, st, a);
     return hx_fail(HX_E_RANGE, "unsupported product shape wn=%d wk=%d for %d m-groups", wn, wk, MG);
 }
 
 // ---- host side: how to cut one product into launches ---------------------------------------------------------------
 // A workgroup occupies a whole compute unit (128 KiB of LDS), so a launch runs in rounds of HX_CUS
-// workgroups.  Measured on MI355X the 4 x 1 shape (four n-tiles sharing one activation stream, 32 KiB
-// stages, a barrier every 8 k-steps) is the fastest; products with a fused epilogue run it over the whole
-// K, products whose consumer kernel sums split partials are cut along K into as many splits (at most
-// HX_MAX_SPLITS, at least 16 k-steps each) as it takes to give every compute unit a workgroup.
-// HX_GEMM_SHAPE="wn,wk,splits" overrides the choice for the split products (tuning).
+// workgroups and a partly filled last round costs a full one.  Measured on MI355X, wn x 1 shapes (wn n-tiles
+// sharing one activation stream, 32 KiB stages, a barrier every 8 k-steps) are the fastest.  The planner
+// picks wn in {4, 5, 6} -- and, for products whose consumer kernel sums split partials, the number of
+// K-splits (at most HX_MAX_SPLITS, at least 16 k-steps each) -- that minimises rounds x tiles per
+// workgroup, i.e. the time of the busiest compute unit; ties go to the smaller wn and fewer splits.
+// Example: the 1184 tiles of the 7B gate|up matrix make 296 workgroups of 4 (two rounds on 256 compute
+// units) but 237 workgroups of 5 (one round).  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
 #define HX_CUS 256
 
 struct gemm_launch { int wn, wk, splits, tile0, tiles; };
 
 static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_launch *out) {
-    gemm_launch l{4, 1, 1, 0, n_tiles};
-    if (partial) {
-        const int groups = (n_tiles + 3) / 4;
-        int s = (HX_CUS + groups / 2) / groups;
-        const int cap = k_steps / 16;
-        if (s > HX_MAX_SPLITS) s = HX_MAX_SPLITS;
-        if (s > cap) s = cap;
-        if (s < 1) s = 1;
-        l.splits = s;
-        int a, b, c;
-        const char *ov = getenv("HX_GEMM_SHAPE");
-        if (ov && sscanf(ov, "%d,%d,%d", &a, &b, &c) == 3 && c >= 1 && c <= HX_MAX_SPLITS && k_steps / (b * c) >= 1 &&
-            ((a == 4 && (b == 1 || b == 2)) || (mg <= 4 && ((a == 2 && b == 4) || (a == 1 && b == 8))))) {
-            l.wn = a; l.wk = b; l.splits = c;
+    gemm_launch best{4, 1, 1, 0, n_tiles};
+    double best_cost = 1e300;
+    const int max_s = partial ? HX_MAX_SPLITS : 1;
+    for (int wn = 4; wn <= 6; ++wn) {
+        for (int s = 1; s <= max_s; ++s) {
+            if (s > 1 && k_steps / s < 16) break;
+            const int wgs = ((n_tiles + wn - 1) / wn) * s;
+            const int rounds = (wgs + HX_CUS - 1) / HX_CUS;
+            const int sps = (k_steps + s - 1) / s;
+            // busiest compute unit: rounds x wn tiles x (k-steps + ring fill), plus a small charge per split
+            // for writing and re-reading its partial tile
+            const double cost = (double)rounds * (wn + 0.35 * (wn - 4)) * (sps + 24.0) * (1.0 + 0.02 * (s - 1));
+            if (cost < best_cost - 1e-9) { best_cost = cost; best.wn = wn; best.splits = s; }
         }
     }
-    out[0] = l;
+    int a, b, c;
+    const char *ov = getenv("HX_GEMM_SHAPE");
+    if (ov && sscanf(ov, "%d,%d,%d", &a, &b, &c) == 3 && c >= 1 && c <= max_s && k_steps / (b * c) >= 1 &&
+        ((b == 1 && a >= 4 && a <= 6) || (a == 4 && b == 2))) {
+        best.wn = a; best.wk = b; best.splits = c;
+    }
+    (void)mg;
+    out[0] = best;
     return 1;
 }
 
