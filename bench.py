@@ -144,7 +144,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
-                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_chunk": eng.attention_chunk()},
+                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves()},
         "step_hbm": {"algorithmic_bytes": nbytes["total"], "weights_bytes": nbytes["weights"], "kv_bytes": nbytes["kv"],
                      "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
                      "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},

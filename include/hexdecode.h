@@ -164,14 +164,13 @@ int hx_set_attn_capture(hx_engine *engine, float *attn_dev);
 
 /* ---- single stages (test and measurement hooks; the same kernels decode_step launches) ------------ */
 
-/* Work list of the split-K attention: sequence b contributes ceil(seq_lens[b] / chunk) items
-   (b, c), listed in batch order; chunk = hx_attention_chunk(engine).  Outputs are DEVICE int32:
-   n_items_out [1], item_seq_out / item_chunk_out [>= batch * ceil(max_seq_len / chunk)],
-   first_item_out [batch + 1] (exclusive prefix sum of the per-sequence item counts). */
-int hx_stage_worklist(hx_engine *engine, int32_t batch, const int32_t *seq_lens, int32_t *n_items_out,
-                      int32_t *item_seq_out, int32_t *item_chunk_out, int32_t *first_item_out,
-                      void *stream);
-int hx_attention_chunk(const hx_engine *engine); /* tokens per split-K work item */
+/* Schedule of the split-K attention.  A tile is the K and V of 16 tokens of one KV head; the tiles of the batch,
+   in (sequence, KV head, block) order, are cut into hx_attention_waves(engine) equal runs, one per wavefront.
+   Outputs are DEVICE int32: prefix_out [batch + 1] = exclusive prefix sum of ceil(seq_lens[b] / 16);
+   sched_out [2] = { tiles per run = ceil(total tiles / waves), total tiles = prefix_out[batch] * n_kv_heads }. */
+int hx_stage_schedule(hx_engine *engine, int32_t batch, const int32_t *seq_lens, int32_t *prefix_out,
+                      int32_t *sched_out, void *stream);
+int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention kernel */
 
 /* bias + RoPE + cache append of one layer: qkv_dev fp32 [batch, qkv_cols] is the projection WITHOUT
    bias (the packed bias of `layer` is added); writes K/V of position positions[b] into `kv` and

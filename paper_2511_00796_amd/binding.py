@@ -20,7 +20,7 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "hx_set_attn_capture", "hx_stage_worklist", "hx_attention_chunk",
+           "decode_step", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
            "hx_profile_enable", "hx_profile_read"]
 
@@ -71,8 +71,8 @@ def load():
         "hx_kv_gather": [vp, C.c_int, vp, vp, vp, vp, i32, i32, i64, vp],
         "decode_step": [vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp],
         "hx_set_attn_capture": [vp, vp],
-        "hx_stage_worklist": [vp, i32, vp, vp, vp, vp, vp, vp],
-        "hx_attention_chunk": [vp],
+        "hx_stage_schedule": [vp, i32, vp, vp, vp, vp],
+        "hx_attention_waves": [vp],
         "hx_stage_rope_append": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_attention": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],
@@ -196,20 +196,15 @@ class Engine:
         return ms.value, n.value
 
     # -- single stages
-    def attention_chunk(self) -> int:
-        return load().hx_attention_chunk(self.handle)
+    def attention_waves(self) -> int:
+        return load().hx_attention_waves(self.handle)
 
-    def stage_worklist(self, seq_lens: torch.Tensor):
+    def stage_schedule(self, seq_lens: torch.Tensor):
         B = seq_lens.numel()
-        chunk = self.attention_chunk()
-        cap = B * ((self.cfg.max_seq_len + chunk - 1) // chunk)
-        n = torch.zeros(1, dtype=torch.int32, device=self.device)
-        iseq = torch.zeros(cap, dtype=torch.int32, device=self.device)
-        ichunk = torch.zeros(cap, dtype=torch.int32, device=self.device)
-        first = torch.zeros(B + 1, dtype=torch.int32, device=self.device)
-        _check(load().hx_stage_worklist(self.handle, B, _ptr(seq_lens), _ptr(n), _ptr(iseq), _ptr(ichunk),
-                                        _ptr(first), _stream()))
-        return n, iseq, ichunk, first
+        prefix = torch.zeros(B + 1, dtype=torch.int32, device=self.device)
+        sched = torch.zeros(2, dtype=torch.int32, device=self.device)
+        _check(load().hx_stage_schedule(self.handle, B, _ptr(seq_lens), _ptr(prefix), _ptr(sched), _stream()))
+        return prefix, sched
 
     def stage_rope_append(self, kv: "KVCache", layer: int, qkv: torch.Tensor, positions, block_table) -> torch.Tensor:
         B = qkv.shape[0]

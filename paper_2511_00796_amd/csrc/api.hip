@@ -52,11 +52,11 @@ static int check_config(const hx_model_config *c) {
     return HX_OK;
 }
 
-static int attention_chunk() {
-    int c = env_int("HX_ATTN_CHUNK", 512);
-    if (c < 16) c = 16;
-    if (c > 1024) c = 1024;
-    return c / 16 * 16;
+static int attention_waves() {      // HX_ATTN_WAVES overrides (tuning)
+    int w = env_int("HX_ATTN_WAVES", 2048);
+    if (w < 64) w = 64;
+    if (w > 16384) w = 16384;
+    return w;
 }
 
 static void init_matrix(hx_matrix *m, size_t *at, int K, int N, bool gate_up) {
@@ -117,12 +117,12 @@ static size_t map_workspace(hx_engine *e) {
     m->qp = take(B * c->n_kv_heads * (size_t)(e->D / 32) * 1024 + 16 * (size_t)e->D * 2);   // + one K tile of slack: the attention
                                                                                           // kernel may read a whole K|V tile starting at any query
     m->cs = take(2 * B * (e->D / 2) * 4);
-    m->item_seq = take((size_t)e->max_items * 4);
-    m->item_chunk = take((size_t)e->max_items * 4);
-    m->first_item = take((B + 1) * 4);
-    m->n_items = take(256);
-    m->part_ml = take((size_t)e->max_items * c->n_kv_heads * 32 * 4);
-    m->part_o = take((size_t)e->max_items * c->n_kv_heads * e->G * e->D * 4);
+    m->pre = take(HX_PREFIX_LEN * 4);
+    m->lens = take(256 * 4);
+    m->sched = take(256);
+    const size_t slots = (size_t)e->attn_waves + B * c->n_kv_heads;
+    m->part_ml = take(slots * 32 * 4);
+    m->part_o = take(slots * e->G * e->D * 4);
     m->amax_val = take(B * e->wlm.n_tiles * 4);
     m->amax_idx = take(B * e->wlm.n_tiles * 4);
     size_t widest = wide;
@@ -141,8 +141,7 @@ static int init_engine_shape(hx_engine *e, const hx_model_config *cfg) {
     derived d = derive(cfg);
     e->G = d.G; e->D = d.D; e->q_dim = d.q_dim; e->kv_dim = d.kv_dim; e->qkv_dim = d.qkv_dim;
     e->m_groups_max = hx_m_groups(cfg->max_batch);
-    e->chunk = attention_chunk();
-    e->max_items = cfg->max_batch * ((cfg->max_seq_len + e->chunk - 1) / e->chunk);
+    e->attn_waves = attention_waves();
     return HX_OK;
 }
 
@@ -222,7 +221,7 @@ extern "C" int hx_engine_destroy(hx_engine *e) {
     return HX_OK;
 }
 
-extern "C" int hx_attention_chunk(const hx_engine *e) { return e ? e->chunk : hx_fail(HX_E_NULL, "engine is NULL"); }
+extern "C" int hx_attention_waves(const hx_engine *e) { return e ? e->attn_waves : hx_fail(HX_E_NULL, "engine is NULL"); }
 
 extern "C" int hx_set_attn_capture(hx_engine *e, float *attn_dev) {
     if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
@@ -413,19 +412,15 @@ extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t
 }
 
 // ---- single stages ---------------------------------------------------------------------------------------------------
-extern "C" int hx_stage_worklist(hx_engine *e, int32_t batch, const int32_t *seq_lens, int32_t *n_items_out,
-                                 int32_t *item_seq_out, int32_t *item_chunk_out, int32_t *first_item_out, void *stream) {
+extern "C" int hx_stage_schedule(hx_engine *e, int32_t batch, const int32_t *seq_lens, int32_t *prefix_out,
+                                 int32_t *sched_out, void *stream) {
     int rc = check_step_args(e, nullptr, batch, 1);
     if (rc) return rc;
-    if (!seq_lens || !n_items_out || !item_seq_out || !item_chunk_out || !first_item_out)
-        return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    if (!seq_lens || !prefix_out || !sched_out) return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
-    const size_t items = (size_t)batch * ((e->cfg.max_seq_len + e->chunk - 1) / e->chunk);
-    HX_CHECK_HIP(hipMemcpyAsync(n_items_out, e->ws + e->map.n_items, 4, hipMemcpyDeviceToDevice, st));
-    HX_CHECK_HIP(hipMemcpyAsync(item_seq_out, e->ws + e->map.item_seq, items * 4, hipMemcpyDeviceToDevice, st));
-    HX_CHECK_HIP(hipMemcpyAsync(item_chunk_out, e->ws + e->map.item_chunk, items * 4, hipMemcpyDeviceToDevice, st));
-    HX_CHECK_HIP(hipMemcpyAsync(first_item_out, e->ws + e->map.first_item, ((size_t)batch + 1) * 4, hipMemcpyDeviceToDevice, st));
+    HX_CHECK_HIP(hipMemcpyAsync(prefix_out, e->ws + e->map.pre, ((size_t)batch + 1) * 4, hipMemcpyDeviceToDevice, st));
+    HX_CHECK_HIP(hipMemcpyAsync(sched_out, e->ws + e->map.sched, 8, hipMemcpyDeviceToDevice, st));
     return HX_OK;
 }
 

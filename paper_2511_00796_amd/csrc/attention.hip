@@ -1,8 +1,16 @@
-// Split-K flash-decoding attention over the paged cache, the work-list builder that flattens the
-// ragged batch into fixed-size KV chunks, and the combine kernel that merges the chunk partials.
+// Split-K flash-decoding attention over the paged cache: the per-step schedule that cuts the ragged
+// batch into equal shares of K/V tiles, the attention kernel, and the combine kernel that merges the
+// partial results.
 //
-// One wavefront owns one (sequence, KV head, chunk) item and serves all G query heads of that KV
-// head at once, so every K and V byte is read exactly once:
+// Work decomposition ("stream-K").  A tile is the K and V of 16 tokens of one KV head.  All tiles of the
+// batch are lined up in (sequence, KV head, block) order and cut into W equal runs of S = ceil(Nt / W)
+// tiles, one run per wavefront, W = 8 per compute unit.  Every wavefront therefore streams the same
+// number of bytes whatever the length mix, all of them are resident at once and finish together, and a
+// run is long (about 1 MiB at the 7B shape), so start-up latency is paid once.  A run that crosses from
+// one (sequence, KV head) pair into the next emits one partial result per pair it touches; run w and pair
+// p write slot w + p, which is unique and makes the slots of a pair contiguous (w0 + p .. w1 + p).
+//
+// One wavefront serves all G query heads of its KV head at once, so every K and V byte is read exactly once:
 //     S^T[token, g] = K_tile[token, :] . q[g, :]        v_mfma_f32_16x16x32_bf16 (A = K tile, B = packed q)
 //     O^T[d, g]    += V_tile^T[d, token] . P^T[token, g] v_mfma_f32_16x16x16_bf16 (A = V tile, B = P)
 // The accumulator layout of the first product (lane = query head g, 4 registers = 4 tokens) is
@@ -14,19 +22,22 @@
 
 #define HX_NEG_BIG (-1.0e30f)
 
-// ---- per-step setup: work list + RoPE angles -------------------------------------------------------------
-// block 0: items.  Sequence b contributes ceil(T_b / chunk) items (b, c) in batch order.
+// ---- per-step setup: schedule + RoPE angles ----------------------------------------------------------------
+// block 0: sched[0] = S (tiles per wavefront), sched[1] = Nt (tiles in all), pre[b] = blocks of the sequences
+// before b (pre[b] = total for b >= batch, HX_PREFIX_LEN entries), lens[b] = seq_lens[b] (0 for b >= batch).
 // blocks 1..batch: cos/sin of pos * theta^(-2i/D), evaluated in double, stored fp32.
-__global__ __launch_bounds__(256) void step_setup_kernel(int batch, int chunk, const int32_t *__restrict__ positions,
+__global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, int n_waves,
+                                                         const int32_t *__restrict__ positions,
                                                          const int32_t *__restrict__ seq_lens,
-                                                         int32_t *__restrict__ item_seq, int32_t *__restrict__ item_chunk,
-                                                         int32_t *__restrict__ first_item, int32_t *__restrict__ n_items,
-                                                         float *__restrict__ cs, int half, double theta, int max_batch) {
+                                                         int32_t *__restrict__ pre, int32_t *__restrict__ lens,
+                                                         int32_t *__restrict__ sched, float *__restrict__ cs, int half,
+                                                         double theta, int max_batch) {
     if (blockIdx.x == 0) {
+        if (seq_lens == nullptr) return;
         __shared__ int32_t scan[256];
-        int b = threadIdx.x;
-        int cnt = 0;
-        if (seq_lens != nullptr && b < batch) cnt = (seq_lens[b] + chunk - 1) / chunk;
+        const int b = threadIdx.x;
+        const int T = b < batch ? seq_lens[b] : 0;
+        const int cnt = (T + 15) >> 4;
         scan[b] = cnt;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {       // inclusive Hillis-Steele scan
@@ -35,13 +46,14 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int chunk, c
             scan[b] += v;
             __syncthreads();
         }
-        if (seq_lens != nullptr) {
-            int start = scan[b] - cnt;
-            if (b < batch) {
-                first_item[b] = start;
-                for (int c = 0; c < cnt; ++c) { item_seq[start + c] = b; item_chunk[start + c] = c; }
-            }
-            if (b == batch - 1) { first_item[batch] = scan[b]; n_items[0] = scan[b]; }
+        const int total = scan[255];
+        pre[b] = scan[b] - cnt;                          // b >= batch: cnt = 0, so pre[b] = total
+        lens[b] = T;
+        for (int i = 256 + b; i < HX_PREFIX_LEN; i += 256) pre[i] = total;
+        if (b == 0) {
+            const long long nt = (long long)total * n_kv;
+            sched[0] = (int)((nt + n_waves - 1) / n_waves);
+            sched[1] = (int)nt;
         }
     } else if (positions != nullptr) {
         int b = blockIdx.x - 1;
@@ -57,10 +69,10 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int chunk, c
 int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
                          hipStream_t st) {
     char *ws = e->ws;
-    hipLaunchKernelGGL(step_setup_kernel, dim3(batch + 1), dim3(256), 0, st, batch, e->chunk, positions, seq_lens,
-                       (int32_t *)(ws + e->map.item_seq), (int32_t *)(ws + e->map.item_chunk),
-                       (int32_t *)(ws + e->map.first_item), (int32_t *)(ws + e->map.n_items),
-                       (float *)(ws + e->map.cs), e->D / 2, (double)e->cfg.rope_theta, e->cfg.max_batch);
+    hipLaunchKernelGGL(step_setup_kernel, dim3(batch + 1), dim3(256), 0, st, batch, e->cfg.n_kv_heads, e->attn_waves,
+                       positions, seq_lens, (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
+                       (int32_t *)(ws + e->map.sched), (float *)(ws + e->map.cs), e->D / 2, (double)e->cfg.rope_theta,
+                       e->cfg.max_batch);
     HX_CHECK_LAUNCH("step_setup");
     return HX_OK;
 }
@@ -77,52 +89,26 @@ __device__ __forceinline__ void load_tile(u32x4_t (&r)[D / 16], const char *tile
     for (int i = 0; i < D / 16; ++i) r[i] = __builtin_nontemporal_load(p + i * 64);
 }
 
-// PF = tiles in flight per wavefront (register ring).  The loop has no prologue and no conditional load:
-// it starts PF tiles early (those iterations see only masked-out tokens and zero operands) and every
-// iteration requests the tile PF ahead into the slot it has just finished with; past the end of the
-// chunk the request goes to the packed query (small, cache-resident, finite), so the load stream is
-// unconditional and the compiler keeps exactly PF - 1 tiles outstanding behind every wait.
-template <int D, int PF>
-__global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict__ pool_layer, size_t block_bytes,
-                                                         const uint16_t *__restrict__ qp,
-                                                         const int32_t *__restrict__ seq_lens,
-                                                         const int32_t *__restrict__ table, int max_blocks,
-                                                         const int32_t *__restrict__ item_seq,
-                                                         const int32_t *__restrict__ item_chunk,
-                                                         const int32_t *__restrict__ n_items, int chunk, int n_kv,
-                                                         int G, float scale_log2e, float *__restrict__ part_ml,
-                                                         float *__restrict__ part_o) {
-    const int item = blockIdx.y;
-    if (item >= n_items[0]) return;
-    const int kvh = blockIdx.x;    // the KV heads of a block are adjacent in the pool: launch them together
-    const int lane = threadIdx.x;
-    const int g = lane & 15, qd = lane >> 4;
-    const int b = item_seq[item], c = item_chunk[item];
-    const int T = seq_lens[b];
-    const int t0 = c * chunk;
-    const int t1 = min(T, t0 + chunk);
-    const int nblk = (t1 - t0 + 15) >> 4;          // 1 .. chunk/16 (<= 64)
-    const size_t head_off = (size_t)kvh * 2 * (16 * D * 2);
-
-    // physical ids of this chunk's blocks: lane i holds block i
-    int32_t my_blk = 0;
-    if (lane < nblk) my_blk = table[(size_t)b * max_blocks + (t0 >> 4) + lane];
-
-    // packed query: B operand of the score product
-    const char *qtile = (const char *)(qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512);
-    bf16x8_t qop[D / 32];
-    {
-        const uint4 *q4 = (const uint4 *)qtile + lane;
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) qop[kk] = __builtin_bit_cast(bf16x8_t, q4[kk * 64]);
-    }
-
+// State of one (sequence, KV head) pair while its tiles stream through.
+template <int D>
+struct AttnState {
     f32x4_t o[D / 16];
-#pragma unroll
-    for (int nn = 0; nn < D / 16; ++nn) o[nn] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m = HX_NEG_BIG;   // running maximum of the scaled scores (base-2 domain), same in the 4 lane groups
-    float l = 0.f;          // this lane's share of the running sum
+    float m;   // running maximum of the scaled scores (base-2 domain), same in the 4 lane groups
+    float l;   // this lane's share of the running sum
+};
 
+// Streams `nblk` (1..128) consecutive blocks of one pair: tokens [t0, t1), t0 a multiple of 16.  blk_lo / blk_hi
+// hold the physical ids: lane i of blk_lo = block i, lane i of blk_hi = block 64 + i.
+// PF = tiles in flight (register ring).  The loop has no prologue and no conditional load: it starts PF tiles
+// early (those iterations see only masked-out tokens and zero operands) and every iteration requests the tile
+// PF ahead into the slot it has just finished with; past the end of the run the request goes to the packed
+// query (small, cache-resident, finite), so the load stream is unconditional and the compiler keeps exactly
+// PF - 1 tiles outstanding behind every wait.
+template <int D, int PF>
+__device__ __forceinline__ void stream_tiles(AttnState<D> &st, const bf16x8_t (&qop)[D / 32], const char *pool_layer,
+                                             size_t block_bytes, size_t head_off, const char *qtile, int32_t blk_lo,
+                                             int32_t blk_hi, int nblk, int t0, int t1, float scale_log2e, int lane) {
+    const int qd = lane >> 4;
     u32x4_t ring[PF][D / 16];
 #pragma unroll
     for (int s = 0; s < PF; ++s)
@@ -157,15 +143,15 @@ __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict_
             float mx = fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            const float m_new = fmaxf(st.m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
             float p[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s4[r] - m_new);
-            l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-            m = m_new;
+            st.l = st.l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+            st.m = m_new;
 #pragma unroll
-            for (int nn = 0; nn < D / 16; ++nn) o[nn] *= alpha;
+            for (int nn = 0; nn < D / 16; ++nn) st.o[nn] *= alpha;
             // P enters the matrix core as bf16; split it into a high and a low bf16 part so that the
             // product keeps ~16 significant bits of every probability
             uint2 ph, pl;
@@ -178,47 +164,130 @@ __global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict_
 #pragma unroll
             for (int q = 0; q < D / 32; ++q) {
                 uint2 lo = make_uint2(vv[q].x, vv[q].y), hi = make_uint2(vv[q].z, vv[q].w);
-                o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_hi, o[2 * q], 0, 0, 0);
-                o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_hi, o[2 * q + 1], 0, 0, 0);
+                st.o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_hi, st.o[2 * q], 0, 0, 0);
+                st.o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_hi, st.o[2 * q + 1], 0, 0, 0);
             }
 #pragma unroll
             for (int q = 0; q < D / 32; ++q) {
                 uint2 lo = make_uint2(vv[q].x, vv[q].y), hi = make_uint2(vv[q].z, vv[q].w);
-                o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_lo, o[2 * q], 0, 0, 0);
-                o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_lo, o[2 * q + 1], 0, 0, 0);
+                st.o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, lo), pop_lo, st.o[2 * q], 0, 0, 0);
+                st.o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_lo, st.o[2 * q + 1], 0, 0, 0);
             }
-            // the slot is free: request tile i + PF into it (or the query once the chunk is exhausted)
+            // the slot is free: request tile i + PF into it (or the query once the run is exhausted)
             const int nx = i + PF;
-            const int32_t blk = __builtin_amdgcn_readlane(my_blk, nx & 63);
+            const int32_t blk = (nx < 64) ? __builtin_amdgcn_readlane(blk_lo, nx & 63) : __builtin_amdgcn_readlane(blk_hi, nx & 63);
             const char *src = (nx < nblk) ? pool_layer + (size_t)blk * block_bytes + head_off : qtile;
             load_tile<D>(ring[s], src, lane);
         }
     }
-    // total of the running sum over the four lane groups
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+}
 
-    const size_t pi = (size_t)item * n_kv + kvh;
-    if (qd == 0) {
-        part_ml[pi * 32 + g] = m;
-        part_ml[pi * 32 + 16 + g] = l;
-    }
-    if (g < G) {
-        float *po = part_o + (pi * G + g) * D;
+template <int D, int PF>
+__global__ __launch_bounds__(64) void attn_splitk_kernel(const char *__restrict__ pool_layer, size_t block_bytes,
+                                                         const uint16_t *__restrict__ qp,
+                                                         const int32_t *__restrict__ table, int max_blocks,
+                                                         const int32_t *__restrict__ pre,
+                                                         const int32_t *__restrict__ lens,
+                                                         const int32_t *__restrict__ sched, int n_kv, int G,
+                                                         float scale_log2e, float *__restrict__ part_ml,
+                                                         float *__restrict__ part_o) {
+    const int w = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int S = sched[0], Nt = sched[1];
+    int f = w * S;
+    const int f1 = min(Nt, f + S);
+    if (f >= f1) return;
+    const int g = lane & 15, qd = lane >> 4;
+
+    // the whole schedule sits in registers: lane l holds pre[l + 64 i] and lens[l + 64 i]
+    int32_t pr[HX_PREFIX_LEN / 64], ln[4];
 #pragma unroll
-        for (int nn = 0; nn < D / 16; ++nn) *(f32x4_t *)(po + nn * 16 + qd * 4) = o[nn];
+    for (int i = 0; i < HX_PREFIX_LEN / 64; ++i) pr[i] = pre[lane + 64 * i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ln[i] = lens[lane + 64 * i];
+    auto pick = [&](const int32_t *regs, int n, int idx) -> int32_t {   // regs[idx / 64] of lane idx % 64
+        int32_t v = 0;
+#pragma unroll
+        for (int i = 0; i < HX_PREFIX_LEN / 64; ++i)
+            if (i < n && (idx >> 6) == i) v = __builtin_amdgcn_readlane(regs[i], idx & 63);
+        return v;
+    };
+
+    while (f < f1) {                                     // one iteration per (sequence, KV head) pair touched
+        // sequence of tile f: the last b with pre[b] * n_kv <= f
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < HX_PREFIX_LEN / 64; ++i) cnt += __popcll(__ballot((long long)pr[i] * n_kv <= (long long)f));
+        const int b = __builtin_amdgcn_readfirstlane(cnt) - 1;
+        const int pb = pick(pr, HX_PREFIX_LEN / 64, b);
+        const int T = pick(ln, 4, b);
+        const int nblk_b = (T + 15) >> 4;
+        const int local = f - pb * n_kv;
+        const int kvh = local / nblk_b;
+        const int blk0 = local - kvh * nblk_b;
+        const int n = min(f1 - f, nblk_b - blk0);        // tiles of this pair in this run
+        const size_t head_off = (size_t)kvh * 2 * (16 * D * 2);
+
+        // packed query: B operand of the score product
+        const char *qtile = (const char *)(qp + ((size_t)b * n_kv + kvh) * (D / 32) * 512);
+        bf16x8_t qop[D / 32];
+        {
+            const uint4 *q4 = (const uint4 *)qtile + lane;
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) qop[kk] = __builtin_bit_cast(bf16x8_t, q4[kk * 64]);
+        }
+        AttnState<D> st;
+#pragma unroll
+        for (int nn = 0; nn < D / 16; ++nn) st.o[nn] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        st.m = HX_NEG_BIG;
+        st.l = 0.f;
+
+        for (int done = 0; done < n; done += 128) {      // at most 128 block ids fit the two id registers
+            const int nsub = min(128, n - done);
+            const int32_t *row = table + (size_t)b * max_blocks + blk0 + done;
+            int32_t blk_lo = (lane < nsub) ? row[lane] : 0;
+            int32_t blk_hi = (64 + lane < nsub) ? row[64 + lane] : 0;
+            const int t0 = (blk0 + done) * 16;
+            // Everything requested so far must have landed before the tile loop is entered: its waits count
+            // outstanding loads, and a load still in flight on entry would make every wait in the loop drain
+            // the tile ring to match.
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) asm volatile("" : "+v"(qop[kk]));
+            asm volatile("" : "+v"(blk_lo), "+v"(blk_hi));
+            stream_tiles<D, PF>(st, qop, pool_layer, block_bytes, head_off, qtile, blk_lo, blk_hi, nsub, t0,
+                                min(T, t0 + nsub * 16), scale_log2e, lane);
+        }
+
+        // total of the running sum over the four lane groups
+        float l = st.l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const size_t slot = (size_t)w + (size_t)b * n_kv + kvh;
+        if (qd == 0) {
+            part_ml[slot * 32 + g] = st.m;
+            part_ml[slot * 32 + 16 + g] = l;
+        }
+        if (g < G) {
+            float *po = part_o + (slot * G + g) * D;
+#pragma unroll
+            for (int nn = 0; nn < D / 16; ++nn) *(f32x4_t *)(po + nn * 16 + qd * 4) = st.o[nn];
+        }
+        f += n;
     }
 }
 
 // ---- combine ---------------------------------------------------------------------------------------------
-// o = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of the sequence.
-// One wavefront per (sequence, query head): lane = (phase 0..3, d8 0..15); phase p takes chunks p, p+4, ...
+// o = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the partial results of the pair (sequence, KV head):
+// the runs w0..w1 that cover its tiles, found from the schedule, in slots w + pair.
+// One wavefront per (sequence, query head): lane = (phase 0..3, d8 0..15); phase p takes partials p, p+4, ...
 // in order, then the four phases are summed by a fixed shuffle tree (deterministic).  Lanes of phase 0
 // write the bf16-rounded result into the packed activation buffer of the output projection and, if asked,
 // the unrounded fp32 values.  D = 64 uses lanes d8 < 8 only.
 template <int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, int n_kv, int G,
-                                                           const int32_t *__restrict__ first_item,
+                                                           const int32_t *__restrict__ pre,
+                                                           const int32_t *__restrict__ lens,
+                                                           const int32_t *__restrict__ sched,
                                                            const float *__restrict__ part_ml,
                                                            const float *__restrict__ part_o,
                                                            uint16_t *__restrict__ ap, int m_groups,
@@ -229,21 +298,24 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
     const bool has_d = d8 < D / 8;
     const int b = bh / n_q, h = bh % n_q;
     const int kvh = h / G, g = h % G;
-    const int i0 = first_item[b], i1 = first_item[b + 1];
+    const int S = sched[0];
+    const int nblk_b = (lens[b] + 15) >> 4;
+    const int start = pre[b] * n_kv + kvh * nblk_b;      // tiles of this pair: [start, start + nblk_b)
+    const int pair = b * n_kv + kvh;
+    const int s0 = start / S + pair, s1 = (start + nblk_b - 1) / S + pair;   // its slots, inclusive
     float M = HX_NEG_BIG;
-    for (int it = i0 + ph; it < i1; it += 4) M = fmaxf(M, part_ml[((size_t)it * n_kv + kvh) * 32 + g]);
+    for (int it = s0 + ph; it <= s1; it += 4) M = fmaxf(M, part_ml[(size_t)it * 32 + g]);
     M = fmaxf(M, __shfl_xor(M, 16));
     M = fmaxf(M, __shfl_xor(M, 32));
     float den = 0.f;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    for (int it = i0 + ph; it < i1; it += 4) {
-        const size_t pi = (size_t)it * n_kv + kvh;
-        const float w = __builtin_amdgcn_exp2f(part_ml[pi * 32 + g] - M);
-        den += w * part_ml[pi * 32 + 16 + g];
+    for (int it = s0 + ph; it <= s1; it += 4) {
+        const float w = __builtin_amdgcn_exp2f(part_ml[(size_t)it * 32 + g] - M);
+        den += w * part_ml[(size_t)it * 32 + 16 + g];
         if (has_d) {
-            const float *po = part_o + (pi * G + g) * D + d8 * 8;
+            const float *po = part_o + ((size_t)it * G + g) * D + d8 * 8;
             const f32x4_t a = *(const f32x4_t *)po, c = *(const f32x4_t *)(po + 4);
             acc[0] += w * a[0]; acc[1] += w * a[1]; acc[2] += w * a[2]; acc[3] += w * a[3];
             acc[4] += w * c[0]; acc[5] += w * c[1]; acc[6] += w * c[2]; acc[7] += w * c[3];
@@ -276,13 +348,13 @@ int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batc
     const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     char *ws = e->ws;
     const int n_kv = e->cfg.n_kv_heads;
-    const int max_items = batch * ((e->cfg.max_seq_len + e->chunk - 1) / e->chunk);
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
-    dim3 grid(n_kv, max_items), block(64);
+    (void)seq_lens; (void)batch;
+    dim3 grid(e->attn_waves), block(64);
 #define HX_ATTN_ARGS                                                                                             \
-    pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), seq_lens, table, max_blocks,                \
-        (const int32_t *)(ws + e->map.item_seq), (const int32_t *)(ws + e->map.item_chunk),                      \
-        (const int32_t *)(ws + e->map.n_items), e->chunk, n_kv, e->G, scale_log2e,                               \
+    pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), table, max_blocks,                          \
+        (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
+        (const int32_t *)(ws + e->map.sched), n_kv, e->G, scale_log2e,                                           \
         (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_kernel<128, 3>), grid, block, 0, st, HX_ATTN_ARGS);
     else             hipLaunchKernelGGL((attn_splitk_kernel<64, 4>), grid, block, 0, st, HX_ATTN_ARGS);
@@ -297,7 +369,8 @@ int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStr
     const int m_groups = hx_m_groups(batch);
     dim3 cgrid((batch * n_q + 3) / 4), cblock(256);
 #define HX_COMB_ARGS                                                                                             \
-    batch, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.first_item), (const float *)(ws + e->map.part_ml),     \
+    batch, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),             \
+        (const int32_t *)(ws + e->map.sched), (const float *)(ws + e->map.part_ml),                              \
         (const float *)(ws + e->map.part_o), (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out
     if (e->D == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, cblock, 0, st, HX_COMB_ARGS);
     else             hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, cblock, 0, st, HX_COMB_ARGS);

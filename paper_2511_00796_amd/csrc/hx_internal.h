@@ -39,6 +39,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define HX_WAVE 64
 #define HX_BLOCK_TOKENS 16
 #define HX_MAX_HIDDEN 8192
+#define HX_PREFIX_LEN 320    // entries of the per-step block prefix (max_batch 256 + 1, padded to 5 x 64)
 #define HX_MAX_SPLITS 9       // K-splits of a product whose partials are summed by its consumer kernel
 
 // ---- error reporting (api.hip) -------------------------------------------------------------------
@@ -117,9 +118,9 @@ struct hx_ws_map {          // byte offsets in the workspace
     size_t ypart;           // fp32 [max_splits][max_batch][max(qkv_dim, hidden)] product partials
     size_t qp;              // bf16 packed queries [max_batch][n_kv][D/32][64][8]
     size_t cs;              // fp32 [max_batch][D/2] cos, then [max_batch][D/2] sin
-    size_t item_seq, item_chunk, first_item, n_items;   // int32 work list
-    size_t part_ml;         // fp32 [max_items][n_kv][32]   running max (16) | sum (16)
-    size_t part_o;          // fp32 [max_items][n_kv][G][D] unnormalised partial outputs
+    size_t pre, lens, sched;  // int32 attention schedule: block prefix [HX_PREFIX_LEN], lengths [256], {S, Nt}
+    size_t part_ml;         // fp32 [slots][32]     running max (16) | sum (16); slots = attn_waves + max_batch*n_kv
+    size_t part_o;          // fp32 [slots][G][D]   unnormalised partial outputs
     size_t amax_val, amax_idx;  // fp32 / int32 [max_batch][lm n_tiles]
     size_t scratch_f32;     // fp32 [max_batch][max(hidden, q_dim, inter, qkv_dim)] stage-hook staging
     size_t total;
@@ -129,8 +130,7 @@ struct hx_engine {
     hx_model_config cfg;
     int G, D, q_dim, kv_dim, qkv_dim;
     int m_groups_max;       // ceil(max_batch / 32)
-    int chunk;              // tokens per split-K attention item
-    int max_items;          // max_batch * ceil(max_seq_len / chunk)
+    int attn_waves;         // wavefronts of the attention kernel (8 per compute unit)
     char *weights;          // device
     char *ws;               // device
     size_t weights_bytes, ws_bytes;

@@ -78,33 +78,33 @@ def test_prefill_fill_and_gather_round_trip_bit_exact(hx, name):
     assert torch.equal(kg2[a:a + 16].cpu().view(torch.int16), k[a + 16:b].view(torch.int16))
 
 
-def test_worklist_matches_host_recomputation(hx):
+def test_schedule_matches_host_recomputation(hx):
     shape = STAGE_SHAPES["d128_g6"]
     eng = build_engine(hx, shape, 3, 64, 16400)
-    chunk = eng.attention_chunk()
+    waves = eng.attention_waves()
     rng = np.random.default_rng(5)
-    lens = rng.integers(1, 16400, size=64).astype(np.int32)
-    lens[:4] = [1, chunk, chunk + 1, 16400]
-    n, iseq, ichunk, first = eng.stage_worklist(dev(lens))
-    torch.cuda.synchronize()
-    cnt = (lens.astype(np.int64) + chunk - 1) // chunk
-    exp_first = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
-    assert int(n.item()) == int(cnt.sum())
-    assert np.array_equal(first.cpu().numpy(), exp_first)
-    exp_seq = np.repeat(np.arange(64, dtype=np.int32), cnt)
-    exp_chunk = np.concatenate([np.arange(c, dtype=np.int32) for c in cnt])
-    assert np.array_equal(iseq.cpu().numpy()[: len(exp_seq)], exp_seq)
-    assert np.array_equal(ichunk.cpu().numpy()[: len(exp_chunk)], exp_chunk)
+    for batch in (64, 3, 1):
+        lens = rng.integers(1, 16400, size=batch).astype(np.int32)
+        lens[0] = 16400
+        if batch > 2:
+            lens[1:3] = [1, 16]
+        prefix, sched = eng.stage_schedule(dev(lens))
+        torch.cuda.synchronize()
+        nblk = (lens.astype(np.int64) + 15) // 16
+        exp_prefix = np.concatenate([[0], np.cumsum(nblk)]).astype(np.int32)
+        assert np.array_equal(prefix.cpu().numpy(), exp_prefix)
+        nt = int(nblk.sum()) * shape.n_kv_heads
+        assert sched.cpu().numpy().tolist() == [(nt + waves - 1) // waves, nt]
 
 
 @pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1"])
 def test_attention_stage_matches_oracle(hx, name):
-    """Lengths cover: a single key, partial / exact / just-over one block, one chunk exactly, chunk
-    boundaries +-1, and several chunks with a ragged tail."""
+    """Lengths cover: a single key, partial / exact / just-over one block, runs that end inside, at and just
+    past block boundaries, and sequences long enough to be cut over many wavefronts (the split points depend on
+    the whole batch, so every pair ends up with a different mix of partial results)."""
     shape = STAGE_SHAPES[name]
     eng = build_engine(hx, shape, 3, 16, 4096)
-    chunk = eng.attention_chunk()
-    lens = [1, 2, 15, 16, 17, 31, 100, chunk - 1, chunk, chunk + 1, 2 * chunk + 5, 3000, 4096, 48, 333, 1024]
+    lens = [1, 2, 15, 16, 17, 31, 100, 511, 512, 513, 1029, 3000, 4096, 48, 333, 1024]
     kv, okv, cfg, table, start, k, v = filled_cache(hx, eng, shape, lens, 21)
     rng = np.random.default_rng(8)
     q = rng.normal(0, 1.2, size=(len(lens), shape.q_dim)).astype(np.float32)
