@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32)
     ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="run only a plain device copy of this size (5 launches): the known traffic against which "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the decode step has no cross-GPU path); "
@@ -75,6 +78,17 @@ def main():
     import torch
 
     from paper_2511_00796_amd import binding, synth, workload
+
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
+        return
 
     binding.load()
     wl = synth.WORKLOADS[args.workload]

@@ -12,7 +12,8 @@ from typing import Dict, Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhexdecode.so")
+# HEXDECODE_LIB points at another build of the same library (e.g. one compiled with different tuning macros)
+LIB_PATH = os.environ.get("HEXDECODE_LIB") or os.path.join(_HERE, "libhexdecode.so")
 
 HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANGE, HX_E_HIP = 0, -1, -2, -3, -4, -5, -6, -7
 (HX_T_EMBED, HX_T_G1, HX_T_WQKV, HX_T_BQKV, HX_T_WO, HX_T_G2, HX_T_WG, HX_T_WU, HX_T_WD, HX_T_GF,

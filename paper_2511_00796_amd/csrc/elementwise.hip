@@ -48,14 +48,24 @@ __global__ __launch_bounds__(HX_NORM_THREADS) void norm_kernel(float *__restrict
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { v[it][j] = a[j]; v[it][4 + j] = c[j]; }
                 if (MODE == 1) {
+                    // all split partials are requested before the first is used (one memory round trip instead
+                    // of one per split); they are added in split order
+                    f32x4_t ya[HX_MAX_SPLITS], yc[HX_MAX_SPLITS];
+#pragma unroll
+                    for (int s = 0; s < HX_MAX_SPLITS; ++s) {
+                        const float *yp = ypart + min(s, splits - 1) * split_stride + (size_t)b * H + i0;
+                        ya[s] = *(const f32x4_t *)yp;
+                        yc[s] = *(const f32x4_t *)(yp + 4);
+                    }
                     float add[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) add[j] = 0.f;
-                    for (int s = 0; s < splits; ++s) {
-                        const float *yp = ypart + s * split_stride + (size_t)b * H + i0;
-                        const f32x4_t ya = *(const f32x4_t *)yp, yc = *(const f32x4_t *)(yp + 4);
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) { add[j] += ya[j]; add[4 + j] += yc[j]; }
+                    for (int s = 0; s < HX_MAX_SPLITS; ++s) {
+                        if (s < splits) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) { add[j] += ya[s][j]; add[4 + j] += yc[s][j]; }
+                        }
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j) v[it][j] += add[j];

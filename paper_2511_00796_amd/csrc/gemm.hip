@@ -11,6 +11,7 @@
 // Epilogues: plain fp32 partials; SiLU(gate) * up -> bf16 packed activations of the down
 // projection; logits + per-tile argmax candidates.
 #include "hx_internal.h"
+#include <algorithm>
 
 // ---- weight packing ------------------------------------------------------------------------------------------
 // grid (n_tiles, ceil(k_steps / 4)), 256 threads: one wavefront per (n_tile, k_step).
@@ -59,7 +60,9 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 // k-slice, 32 KiB per stage) from L2 straight into a four-stage LDS buffer; one workgroup barrier per chunk
 // hands a stage over.  With up to 96 KiB of activations in flight per compute unit the copy keeps pace with
 // the weight stream at HBM speed.
+#ifndef HX_GEMM_RING
 #define HX_GEMM_RING 16
+#endif
 #define HX_GEMM_NBUF 4
 
 struct GemmArgs {
@@ -380,16 +383,18 @@ struct gemm_launch { int wn, wk, splits, tile0, tiles; };
 static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_launch *out) {
     gemm_launch best{4, 1, 1, 0, n_tiles};
     double best_cost = 1e300;
-    const int max_s = partial ? HX_MAX_SPLITS : 1;
+    int max_s = partial ? HX_MAX_SPLITS : 1;
+    if (const char *cap = getenv("HX_GEMM_MAX_SPLITS")) max_s = partial ? std::max(1, std::min(HX_MAX_SPLITS, atoi(cap))) : 1;
     for (int wn = 4; wn <= 6; ++wn) {
         for (int s = 1; s <= max_s; ++s) {
             if (s > 1 && k_steps / s < 16) break;
             const int wgs = ((n_tiles + wn - 1) / wn) * s;
             const int rounds = (wgs + HX_CUS - 1) / HX_CUS;
             const int sps = (k_steps + s - 1) / s;
-            // busiest compute unit: rounds x wn tiles x (k-steps + ring fill), plus a small charge per split
-            // for writing and re-reading its partial tile
-            const double cost = (double)rounds * (wn + 0.35 * (wn - 4)) * (sps + 24.0) * (1.0 + 0.02 * (s - 1));
+            // busiest compute unit: rounds x wn tiles x whole ring revolutions (one more to fill the ring), plus
+            // a small charge per split for writing and re-reading its partial tile
+            const int revolutions = (sps + HX_GEMM_RING - 1) / HX_GEMM_RING + 1;
+            const double cost = (double)rounds * (wn + 0.35 * (wn - 4)) * revolutions * (1.0 + 0.02 * (s - 1));
             if (cost < best_cost - 1e-9) { best_cost = cost; best.wn = wn; best.splits = s; }
         }
     }

@@ -102,13 +102,22 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
     const int slot = pos & 15;
 
     auto gather8 = [&](int col, float *out) {            // sum of the split partials + bias, 8 consecutive columns
+        // every partial is requested before the first is used; they are added in split order
+        f32x4_t ya[HX_MAX_SPLITS], yc[HX_MAX_SPLITS];
+#pragma unroll
+        for (int sp = 0; sp < HX_MAX_SPLITS; ++sp) {
+            const float *src = ypart + min(sp, splits - 1) * split_stride + (size_t)b * qkv_dim + col;
+            ya[sp] = *(const f32x4_t *)src;
+            yc[sp] = *(const f32x4_t *)(src + 4);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) out[j] = 0.f;
-        for (int sp = 0; sp < splits; ++sp) {
-            const float *src = ypart + sp * split_stride + (size_t)b * qkv_dim + col;
-            const f32x4_t a = *(const f32x4_t *)src, c = *(const f32x4_t *)(src + 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { out[j] += a[j]; out[4 + j] += c[j]; }
+        for (int sp = 0; sp < HX_MAX_SPLITS; ++sp) {
+            if (sp < splits) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { out[j] += ya[sp][j]; out[4 + j] += yc[sp][j]; }
+            }
         }
         if (has_bias) {
             const uint4 raw = *(const uint4 *)(bias + col);
