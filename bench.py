@@ -20,6 +20,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 
+# HBM bytes per attention launch at workload 7b-b128 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain
+# copy (profiles/attn_splitk_7b-b128_hbm_traffic.txt).  Valid only for the kernel source they were taken with.
+PMC_TRAFFIC = {"workload": "7b-b128",
+               "attention_hip_sha256": "4a227dd9cf72834b032f3156d0701c4489cc8f51b3d970119d78a90ff64d1a35",
+               "fetch_bytes": 2165.57e6, "write_bytes": 9.45e6}
+
+
+def measured_traffic(workload_name):
+    import hashlib
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2511_00796_amd", "csrc", "attention.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if sha != PMC_TRAFFIC["attention_hip_sha256"] or workload_name != PMC_TRAFFIC["workload"]:
+        return None                      # the kernel changed since the counters were taken
+    return PMC_TRAFFIC["fetch_bytes"] + PMC_TRAFFIC["write_bytes"]
+
+
 def cpu_baseline(wl, dw_host, sample_rows, sample_layers):
     """Time the CPU oracle, as it stands, on a bounded sample of the same workload: `sample_rows`
     sequences through `sample_layers` layers plus embedding and LM head, then scale the per-layer
@@ -163,7 +182,8 @@ def main():
                      "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
                      "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": "attn_splitk_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
+                     "traffic_unit": "bytes per launch",
                      "launches_timed": int(attn_n), "avg_launch_ms": attn_avg_ms,
                      "algorithmic_bytes_per_launch": kv_bytes_per_launch},
         "setup_s": t_build,
