@@ -91,6 +91,11 @@ def _load(path):
     L.orc_head.restype = C.c_int32
     L.orc_decode_step.restype = C.c_int
     L.orc_num_threads.restype = C.c_int
+    L.orc_uniform_open.restype = C.c_float
+    L.orc_uniform_open.argtypes = [C.c_uint32]
+    L.orc_sample.restype = None
+    L.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.orc_philox4x32_10.restype = None
     return L
 
 
@@ -182,6 +187,40 @@ def silu(x: float) -> float:
 def argmax(x) -> int:
     x = _f32(x)
     return int(lib().orc_argmax(_p(x), C.c_int(x.size)))
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """One block of the counter-based generator: 4 counter words, 2 key words -> 4 output words."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.size == 4 and k.size == 2
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def uniform_open(word: int) -> float:
+    return float(lib().orc_uniform_open(C.c_uint32(word)))
+
+
+def sample(logits, temperature: float, seed: int, rows, positions):
+    """Temperature sample (Gumbel-max over the counter-based generator) of every row of ``logits`` [B, V].
+    Returns (tokens int32 [B], logprobs float32 [B], gaps float32 [B]); gap = best minus runner-up of the
+    perturbed scores."""
+    x = _f32(logits)
+    if x.ndim == 1:
+        x = x[None]
+    B, V = x.shape
+    rows = np.asarray(rows, dtype=np.uint32)
+    positions = np.asarray(positions, dtype=np.uint32)
+    tok = np.zeros(B, dtype=np.int32)
+    lp = np.zeros(B, dtype=np.float32)
+    gap = np.zeros(B, dtype=np.float32)
+    for b in range(B):
+        xb = np.ascontiguousarray(x[b])
+        lib().orc_sample(_p(xb), V, C.c_float(temperature), C.c_uint64(seed), C.c_uint32(int(rows[b])),
+                         C.c_uint32(int(positions[b])), tok[b:].ctypes.data, lp[b:].ctypes.data, gap[b:].ctypes.data)
+    return tok, lp, gap
 
 
 # ---- model-level objects -----------------------------------------------------------------------

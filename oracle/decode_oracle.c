@@ -346,6 +346,63 @@ void orc_full_causal(const orc_config *c, const orc_weights *w, const int32_t *t
     free(s); free(p);
 }
 
+/* ---- sampling and log-probabilities ------------------------------------------------------------
+ * Rollout generation draws several responses per prompt (paper Section 1, stage (i)) and the policy
+ * update needs the behaviour policy's log-probability of every drawn token (GRPO workloads, Section 5),
+ * so the step can end in a temperature sample instead of the arg-max.
+ *
+ * Random numbers come from Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11), written here from its published definition: 10 rounds of
+ *     (c0, c1, c2, c3) <- (hi(M1*c2) ^ c1 ^ k0,  lo(M1*c2),  hi(M0*c0) ^ c3 ^ k1,  lo(M0*c0))
+ * with M0 = 0xD2511F53, M1 = 0xCD9E8D57, the key advanced by (0x9E3779B9, 0xBB67AE85) after every round.
+ * Vocabulary entry i of the row with id `row` at position `pos` uses word i % 4 of the block with
+ * counter (i / 4, row, pos, 0x53414D50) and key (seed low word, seed high word).
+ *
+ * Definition of the draw (Gumbel-max; all of it fp32 -- a floating-point value decides an integer here,
+ * so this is the precision of the decision -- except the log-sum-exp, which is plain fp64):
+ *     z_i = logit_i * (1 / T)            u_i = ((word_i >> 9) + 0.5) * 2^-23   in (0, 1), exact in fp32
+ *     y_i = z_i - log(-log(u_i))         token = lowest index attaining max_i y_i
+ *     logprob = z_token - log(sum_i exp(z_i))
+ * P(token = i) = softmax(z)_i exactly (the Gumbel-max identity).  `gap` returns max y minus the runner-up:
+ * implementations whose log differs in the last bits may disagree only when it is tiny. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+float orc_uniform_open(uint32_t word) { return ((float)(word >> 9) + 0.5f) * (1.0f / 8388608.0f); }
+
+void orc_sample(const float *logits, int V, float temperature, uint64_t seed, uint32_t row, uint32_t pos,
+                int32_t *token, float *logprob, float *gap) {
+    const float inv_t = 1.0f / temperature;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    float best = -INFINITY, second = -INFINITY, zmax = -INFINITY;
+    int32_t best_i = 0;
+    for (int i = 0; i < V; ++i) {
+        const uint32_t ctr[4] = {(uint32_t)(i / 4), row, pos, 0x53414D50u};
+        uint32_t r[4];
+        orc_philox4x32_10(ctr, key, r);
+        const float z = logits[i] * inv_t;
+        const float u = orc_uniform_open(r[i % 4]);
+        const float y = z - logf(-logf(u));
+        if (y > best) { second = best; best = y; best_i = i; }
+        else if (y > second) second = y;
+        if (z > zmax) zmax = z;
+    }
+    double sum = 0.0;
+    for (int i = 0; i < V; ++i) sum += exp((double)(logits[i] * inv_t) - (double)zmax);
+    *token = best_i;
+    *logprob = (float)((double)(logits[best_i] * inv_t) - ((double)zmax + log(sum)));
+    *gap = best - second;
+}
+
 int orc_num_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);

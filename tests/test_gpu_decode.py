@@ -140,6 +140,40 @@ def test_decode_step_is_deterministic_and_tokens_are_argmax_of_logits(hx):
     assert torch.equal(t1, dw.next_tokens)
 
 
+def test_decode_step_can_be_captured_in_a_graph(hx):
+    """decode_step allocates nothing, synchronises nothing and uses no memset, so a caller may capture it
+    into a HIP graph.  The graph is replayed several times with eager work and synchronisations of the
+    program in between, and every replay must reproduce the eager step bit for bit."""
+    from paper_2511_00796_amd import workload
+    wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=40, lo=64, hi=2500)
+    dw = workload.build(wl, n_layers=2)
+    for _ in range(2):                           # first launches set kernel attributes; keep them out of the capture
+        dw.step()
+    torch.cuda.synchronize()
+    ref_logits, ref_tokens = dw.logits.clone(), dw.next_tokens.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            dw.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    scratch = torch.empty(1 << 20, device="cuda")
+    for i in range(4):
+        dw.logits.fill_(float("nan"))
+        dw.next_tokens.fill_(-1)
+        scratch.normal_()                        # eager work of the program between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dw.logits, ref_logits), i
+        assert torch.equal(dw.next_tokens, ref_tokens), i
+        dw.step()                                # an eager step between replays gives the same result too
+        torch.cuda.synchronize()
+        assert torch.equal(dw.logits, ref_logits), i
+
+
 def run_sampled(hx, wl, n_layers, rows, with_floor=False):
     from paper_2511_00796_amd import workload
     shape = wl.shape if n_layers is None else dataclasses.replace(wl.shape, n_layers=n_layers)
