@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32)
     ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--sample", type=float, default=0.0, metavar="T",
+                    help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this size (5 launches): the known traffic against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
@@ -153,13 +155,23 @@ def main():
     eng = dw.engine
     nbytes = dw.bytes()
 
+    if args.sample > 0:
+        s_tok = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+        s_lp = torch.zeros(wl.batch, dtype=torch.float32, device="cuda")
+
+        def one_step():
+            eng.decode_step_sample(dw.kv, dw.tokens, dw.positions, dw.seq_lens_d, dw.table_d, args.sample, wl.seed,
+                                   dw.logits, s_tok, s_lp)
+    else:
+        one_step = dw.step
+
     for _ in range(args.warmup):
-        dw.step()
+        one_step()
     torch.cuda.synchronize()
     eng.profile_enable(["attention"])          # HIP events around the dominant kernel only
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        dw.step()
+        one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     attn_ms, attn_n = eng.profile_read("attention")
@@ -177,7 +189,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
-                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves()},
+                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves(),
+                   "token_choice": ("sample T=%g + logprob" % args.sample) if args.sample > 0 else "greedy"},
         "step_hbm": {"algorithmic_bytes": nbytes["total"], "weights_bytes": nbytes["weights"], "kv_bytes": nbytes["kv"],
                      "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
                      "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
@@ -192,7 +205,7 @@ def main():
     if args.breakdown:
         eng.profile_enable(binding.KERNEL_CLASSES)
         for _ in range(3):
-            dw.step()
+            one_step()
         torch.cuda.synchronize()
         bd = {}
         for k in binding.KERNEL_CLASSES:

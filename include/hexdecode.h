@@ -157,6 +157,25 @@ int decode_step(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *toke
                 const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
                 int32_t max_blocks_per_seq, float *logits_out, int32_t *next_tokens_out, void *stream);
 
+/* The same step ending in a temperature sample instead of the arg-max, with the log-probability of the drawn
+   token under the sampling distribution.  Rollout generation draws several responses per prompt (paper
+   Section 1, stage (i) of the workflow) and the policy update of the GRPO workloads (Section 5) needs the
+   behaviour policy's log-probabilities.  Arguments as decode_step, plus:
+     temperature  > 0, finite.  z_i = logit_i * (1 / temperature), the reciprocal taken once in fp32.
+     seed         key of the counter-based generator Philox4x32-10 (Salmon et al., SC'11): low, high word.
+     row_ids      int32 [batch] DEVICE or NULL: id of each sequence in the generator's counter (NULL: its
+                  index in the batch).  Vocabulary entry i of a row uses word i % 4 of the block with counter
+                  (i / 4, row id, positions[row], 0x53414D50); u = ((word >> 9) + 0.5) * 2^-23.
+     tokens_out   int32 [batch]  argmax_i (z_i - log(-log(u_i))), smallest index on ties (Gumbel-max: the
+                  token is distributed as softmax(z)); all fp32.
+     logprobs_out fp32 [batch]   z_token - log(sum_i exp(z_i)).
+   The draw is a pure function of (logits, temperature, seed, row id, position): repeatable bit for bit.
+   Errors: HX_E_RANGE for a temperature that is not positive and finite, HX_E_NULL for NULL outputs. */
+int decode_step_sample(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *tokens,
+                       const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
+                       int32_t max_blocks_per_seq, float temperature, uint64_t seed, const int32_t *row_ids,
+                       float *logits_out, int32_t *tokens_out, float *logprobs_out, void *stream);
+
 /* Parity hook: when attn_dev is not NULL every following decode_step also writes the attention
    output of every layer BEFORE its bf16 rounding to attn_dev, DEVICE fp32
    [n_layers, batch, n_q_heads * head_dim] (batch = that step's batch).  NULL switches it off. */

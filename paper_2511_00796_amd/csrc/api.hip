@@ -125,6 +125,9 @@ static size_t map_workspace(hx_engine *e) {
     m->part_o = take(slots * e->G * e->D * 4);
     m->amax_val = take(B * e->wlm.n_tiles * 4);
     m->amax_idx = take(B * e->wlm.n_tiles * 4);
+    m->samp_z = take(B * e->wlm.n_tiles * 4);
+    m->samp_m = take(B * e->wlm.n_tiles * 4);
+    m->samp_s = take(B * e->wlm.n_tiles * 4);
     size_t widest = wide;
     if ((size_t)c->intermediate > widest) widest = c->intermediate;
     if ((size_t)e->q_dim > widest) widest = e->q_dim;
@@ -376,9 +379,9 @@ static int check_step_args(const hx_engine *e, const hx_kv *kv, int32_t batch, i
     return HX_OK;
 }
 
-extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
-                           const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
-                           int32_t *next_tokens_out, void *stream) {
+static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                    const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
+                    int32_t *next_tokens_out, float *logprobs_out, const hx_sample_params *sample, void *stream) {
     int rc = check_step_args(e, kv, batch, max_blocks);
     if (rc) return rc;
     if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
@@ -406,9 +409,38 @@ extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t
         const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wd, batch), (size_t)batch * c->hidden, next_gain, st));
     }
-    HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st));
-    HX_TIMED(HX_K_SETUP, hx_launch_argmax_final(e, batch, next_tokens_out, st));
+    if (sample) {
+        HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_SAMPLE, logits_out, nullptr, st, sample));
+        HX_TIMED(HX_K_SETUP, hx_launch_sample_final(e, batch, next_tokens_out, logprobs_out, st));
+    } else {
+        HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st));
+        HX_TIMED(HX_K_SETUP, hx_launch_argmax_final(e, batch, next_tokens_out, st));
+    }
     return HX_OK;
+}
+
+extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                           const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
+                           int32_t *next_tokens_out, void *stream) {
+    return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, next_tokens_out,
+                    nullptr, nullptr, stream);
+}
+
+extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                                  const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks,
+                                  float temperature, uint64_t seed, const int32_t *row_ids, float *logits_out,
+                                  int32_t *tokens_out, float *logprobs_out, void *stream) {
+    if (!(temperature > 0.0f) || !(temperature < 1e30f))
+        return hx_fail(HX_E_RANGE, "temperature %g must be positive and finite", (double)temperature);
+    if (!logprobs_out) return hx_fail(HX_E_NULL, "logprobs_out is NULL");
+    hx_sample_params sp;
+    sp.positions = positions;
+    sp.row_ids = row_ids;
+    sp.inv_temperature = 1.0f / temperature;
+    sp.key0 = (uint32_t)seed;
+    sp.key1 = (uint32_t)(seed >> 32);
+    return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, tokens_out,
+                    logprobs_out, &sp, stream);
 }
 
 // ---- single stages ---------------------------------------------------------------------------------------------------

@@ -73,8 +73,13 @@ struct GemmArgs {
     float *y;             // PARTIAL: [splits][M][N]; LOGITS: [M][N] or NULL
     size_t split_stride;  // elements between splits of y
     uint16_t *mp;         // SWIGLU: packed bf16 output
-    float *amax_val;      // LOGITS: [M][n_tiles]
+    float *amax_val;      // LOGITS: [M][n_tiles]; SAMPLE: best perturbed score of the tile
     int32_t *amax_idx;
+    // SAMPLE only
+    const int32_t *positions, *row_ids;
+    float inv_t;
+    uint32_t key0, key1;
+    float *samp_z, *samp_m, *samp_s;   // [M][n_tiles]
 };
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -84,6 +89,20 @@ __device__ __forceinline__ u32x4_t hx_stream_load(const uint4 *p) {   // read-on
 
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
 #define HX_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), from its published definition: ten rounds of
+// (c0, c1, c2, c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0)), key += (W0, W1) per round.
+__device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
 
 template <int MG, int WK> struct GemmGeom {
     static constexpr int KC0 = 32 / (WK * MG);
@@ -104,7 +123,9 @@ template <int MG, int WN, int WK, int EPI>
 __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_stream_kernel(
     const uint4 *__restrict__ a_wp, const uint4 *__restrict__ a_xp, int a_k_steps, int a_n_tiles, int a_tile0,
     int a_tile_end, int a_steps_per_split, int a_steps_per_wave, int a_M, int a_N, float *__restrict__ a_y, size_t a_split_stride,
-    uint16_t *__restrict__ a_mp, float *__restrict__ a_amax_val, int32_t *__restrict__ a_amax_idx) {
+    uint16_t *__restrict__ a_mp, float *__restrict__ a_amax_val, int32_t *__restrict__ a_amax_idx,
+    const int32_t *__restrict__ a_positions, const int32_t *__restrict__ a_row_ids, float a_inv_t, uint32_t a_key0,
+    uint32_t a_key1, float *__restrict__ a_samp_z, float *__restrict__ a_samp_m, float *__restrict__ a_samp_s) {
     using GG = GemmGeom<MG, WK>;
     constexpr int RING = HX_GEMM_RING, NBUF = HX_GEMM_NBUF;
     constexpr int KC = GG::KC, CPR = RING / KC, SLICE_U4 = GG::SLICE_U4, NC = WN * WK;
@@ -301,7 +322,7 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                 }
             }
         }
-    } else {
+    } else if (EPI == HX_EPI_LOGITS) {
         // logits and the best (value, index) of this lane's 16 columns, ascending column order
 #pragma unroll
         for (int g = 0; g < MG; ++g) {
@@ -328,12 +349,66 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                 a_amax_idx[(size_t)m * a_n_tiles + nt] = best_n;
             }
         }
+    } else {
+        // Temperature sample by Gumbel-max, and the pieces of the log-sum-exp: per (row, tile) the best perturbed
+        // score y = z + g with its column and its z, the tile's max of z and its sum of exp(z - max).
+        // z = logit * (1/T); g = -log(-log(u)); u from one generator block per 4 consecutive columns.
+#pragma unroll
+        for (int g = 0; g < MG; ++g) {
+            const int m = 32 * g + ml;
+            const bool row_ok = m < a_M;
+            const uint32_t row = row_ok ? (a_row_ids ? (uint32_t)a_row_ids[m] : (uint32_t)m) : 0u;
+            const uint32_t pos = row_ok ? (uint32_t)a_positions[m] : 0u;
+            float best = -INFINITY, best_z = 0.f, zmax = -INFINITY;
+            int best_n = 0x7fffffff;
+            float z[16];
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                const int n = 32 * nt + 8 * j4 + 4 * hl;
+                uint32_t w[4];
+                hx_philox4x32_10((uint32_t)(n >> 2), row, pos, 0x53414D50u, a_key0, a_key1, w);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float zi = acc[g][4 * j4 + i] * a_inv_t;
+                    z[4 * j4 + i] = (n + i < a_N) ? zi : -INFINITY;
+                    const float u = ((float)(w[i] >> 9) + 0.5f) * (1.0f / 8388608.0f);
+                    const float y = zi - logf(-logf(u));
+                    if (n + i < a_N) {
+                        if (y > best) { best = y; best_n = n + i; best_z = zi; }
+                        zmax = fmaxf(zmax, zi);
+                    }
+                }
+                if (a_y != nullptr && row_ok && n < a_N)
+                    *(f32x4_t *)(a_y + (size_t)m * a_N + n) =
+                        f32x4_t{acc[g][4 * j4], acc[g][4 * j4 + 1], acc[g][4 * j4 + 2], acc[g][4 * j4 + 3]};
+            }
+            // the two half-wavefronts hold the two halves of the tile's 32 columns
+            const float tmax = fmaxf(zmax, __shfl_xor(zmax, 32));
+            float sum = 0.f;
+            if (tmax > -INFINITY) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += expf(z[i] - tmax);     // exp(-inf) = 0 for columns past N
+            }
+            sum += __shfl_xor(sum, 32);
+            const float oy = __shfl_xor(best, 32), oz = __shfl_xor(best_z, 32);
+            const int on = __shfl_xor(best_n, 32);
+            if (oy > best || (oy == best && on < best_n)) { best = oy; best_n = on; best_z = oz; }
+            if (hl == 0 && row_ok) {
+                const size_t o = (size_t)m * a_n_tiles + nt;
+                a_amax_val[o] = best;
+                a_amax_idx[o] = best_n;
+                a_samp_z[o] = best_z;
+                a_samp_m[o] = tmax;
+                a_samp_s[o] = sum;
+            }
+        }
     }
 }
 
 // ---- host side: one launch of a given shape -----------------------------------------------------------------------
 #define HX_GEMM_ARGS a.wp, a.xp, a.k_steps, a.n_tiles, a.tile0, a.tile_end, a.steps_per_split, a.steps_per_wave, a.M, a.N, a.y, \
-                     a.split_stride, a.mp, a.amax_val, a.amax_idx
+                     a.split_stride, a.mp, a.amax_val, a.amax_idx, a.positions, a.row_ids, a.inv_t, a.key0, a.key1, a.samp_z, a.samp_m, \
+                     a.samp_s
 
 template <int MG, int WN, int WK, int EPI>
 static int launch_one(dim3 grid, hipStream_t st, const GemmArgs &a) {
@@ -353,6 +428,7 @@ template <int MG, int WN, int WK>
 static int launch_epi(int epilogue, dim3 grid, hipStream_t st, const GemmArgs &a) {
     if (epilogue == HX_EPI_PARTIAL) return launch_one<MG, WN, WK, HX_EPI_PARTIAL>(grid, st, a);
     if (epilogue == HX_EPI_SWIGLU) return launch_one<MG, WN, WK, HX_EPI_SWIGLU>(grid, st, a);
+    if (epilogue == HX_EPI_SAMPLE) return launch_one<MG, WN, WK, HX_EPI_SAMPLE>(grid, st, a);
     return launch_one<MG, WN, WK, HX_EPI_LOGITS>(grid, st, a);
 }
 
@@ -416,7 +492,8 @@ int hx_gemm_splits(const hx_matrix *m, int batch) {
 }
 
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue, float *y,
-                   void *mp_out, hipStream_t st) {
+                   void *mp_out, hipStream_t st, const hx_sample_params *sample) {
+    if (epilogue == HX_EPI_SAMPLE && !sample) return hx_fail(HX_E_NULL, "sampling parameters missing");
     const int mg = hx_m_groups(batch);
     const bool partial = epilogue == HX_EPI_PARTIAL;
     gemm_launch plan[2];
@@ -439,6 +516,14 @@ int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void
         a.mp = (uint16_t *)mp_out;
         a.amax_val = (float *)(e->ws + e->map.amax_val);
         a.amax_idx = (int32_t *)(e->ws + e->map.amax_idx);
+        a.positions = sample ? sample->positions : nullptr;
+        a.row_ids = sample ? sample->row_ids : nullptr;
+        a.inv_t = sample ? sample->inv_temperature : 1.0f;
+        a.key0 = sample ? sample->key0 : 0u;
+        a.key1 = sample ? sample->key1 : 0u;
+        a.samp_z = (float *)(e->ws + e->map.samp_z);
+        a.samp_m = (float *)(e->ws + e->map.samp_m);
+        a.samp_s = (float *)(e->ws + e->map.samp_s);
         dim3 grid((pl.tiles + pl.wn - 1) / pl.wn, pl.splits);
         int rc;
         switch (mg) {
@@ -484,5 +569,59 @@ int hx_launch_argmax_final(const hx_engine *e, int batch, int32_t *tokens_out, h
     hipLaunchKernelGGL(argmax_final_kernel, dim3(batch), dim3(256), 0, st, (const float *)(e->ws + e->map.amax_val),
                        (const int32_t *)(e->ws + e->map.amax_idx), e->wlm.n_tiles, tokens_out);
     HX_CHECK_LAUNCH("argmax_final");
+    return HX_OK;
+}
+
+// ---- sampled token and its log-probability: reduce the per-tile pieces of each row -----------------------------
+// grid = batch, 256 threads.  Largest perturbed score wins (ties: smaller column); log-sum-exp of the scaled
+// logits = M + log(sum_t s_t exp(m_t - M)) with M = max_t m_t; logprob = z_token - that.  Fixed tree: deterministic.
+__global__ __launch_bounds__(256) void sample_final_kernel(const float *__restrict__ val, const int32_t *__restrict__ idx,
+                                                           const float *__restrict__ zc, const float *__restrict__ tm,
+                                                           const float *__restrict__ tsum, int n_tiles,
+                                                           int32_t *__restrict__ tok_out, float *__restrict__ lp_out) {
+    __shared__ float sv[256], sz[256], sm[256];
+    __shared__ int32_t si[256];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const size_t base = (size_t)m * n_tiles;
+    float best = -INFINITY, bz = 0.f, mx = -INFINITY;
+    int32_t bi = 0x7fffffff;
+    for (int t = tid; t < n_tiles; t += 256) {
+        const float v = val[base + t];
+        const int32_t i = idx[base + t];
+        if (v > best || (v == best && i < bi)) { best = v; bi = i; bz = zc[base + t]; }
+        mx = fmaxf(mx, tm[base + t]);
+    }
+    sv[tid] = best; si[tid] = bi; sz[tid] = bz; sm[tid] = mx;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) {
+            const float v = sv[tid + off]; const int32_t i = si[tid + off];
+            if (v > sv[tid] || (v == sv[tid] && i < si[tid])) { sv[tid] = v; si[tid] = i; sz[tid] = sz[tid + off]; }
+            sm[tid] = fmaxf(sm[tid], sm[tid + off]);
+        }
+        __syncthreads();
+    }
+    const float M = sm[0];
+    __syncthreads();
+    float part = 0.f;
+    for (int t = tid; t < n_tiles; t += 256) part += tsum[base + t] * expf(tm[base + t] - M);
+    sm[tid] = part;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) sm[tid] += sm[tid + off];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        tok_out[m] = si[0];
+        lp_out[m] = sz[0] - (M + logf(sm[0]));
+    }
+}
+
+int hx_launch_sample_final(const hx_engine *e, int batch, int32_t *tokens_out, float *logprobs_out, hipStream_t st) {
+    hipLaunchKernelGGL(sample_final_kernel, dim3(batch), dim3(256), 0, st, (const float *)(e->ws + e->map.amax_val),
+                       (const int32_t *)(e->ws + e->map.amax_idx), (const float *)(e->ws + e->map.samp_z),
+                       (const float *)(e->ws + e->map.samp_m), (const float *)(e->ws + e->map.samp_s), e->wlm.n_tiles,
+                       tokens_out, logprobs_out);
+    HX_CHECK_LAUNCH("sample_final");
     return HX_OK;
 }

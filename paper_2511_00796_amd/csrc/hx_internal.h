@@ -121,7 +121,8 @@ struct hx_ws_map {          // byte offsets in the workspace
     size_t pre, lens, sched;  // int32 attention schedule: block prefix [HX_PREFIX_LEN], lengths [256], {S, Nt}
     size_t part_ml;         // fp32 [slots][32]     running max (16) | sum (16); slots = attn_waves + max_batch*n_kv
     size_t part_o;          // fp32 [slots][G][D]   unnormalised partial outputs
-    size_t amax_val, amax_idx;  // fp32 / int32 [max_batch][lm n_tiles]
+    size_t amax_val, amax_idx;  // fp32 / int32 [max_batch][lm n_tiles]   (sampling: best perturbed score and its column)
+    size_t samp_z, samp_m, samp_s;  // fp32 [max_batch][lm n_tiles]: scaled logit of the candidate, tile max, tile sum of exp
     size_t scratch_f32;     // fp32 [max_batch][max(hidden, q_dim, inter, qkv_dim)] stage-hook staging
     size_t total;
 };
@@ -172,9 +173,19 @@ int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStr
 // gemm.hip
 int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *src, int64_t rows, int64_t cols,
                           int col_phase /*0 plain, 1 gate, 2 up*/, hipStream_t st);
-enum { HX_EPI_PARTIAL = 0, HX_EPI_SWIGLU = 1, HX_EPI_LOGITS = 2 };
+enum { HX_EPI_PARTIAL = 0, HX_EPI_SWIGLU = 1, HX_EPI_LOGITS = 2, HX_EPI_SAMPLE = 3 };
+
+// parameters of a sampled step (NULL = greedy)
+struct hx_sample_params {
+    const int32_t *positions;   // device [batch]: enters the generator's counter
+    const int32_t *row_ids;     // device [batch] or NULL (row id = index in the batch)
+    float inv_temperature;
+    uint32_t key0, key1;        // seed, low and high word
+};
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue,
-                   float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st);
+                   float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st,
+                   const hx_sample_params *sample = nullptr);
+int hx_launch_sample_final(const hx_engine *e, int batch, int32_t *tokens_out, float *logprobs_out, hipStream_t st);
 int hx_gemm_splits(const hx_matrix *m, int batch);   // K-splits the planner uses for a product with split partials
 int hx_launch_argmax_final(const hx_engine *e, int batch, int32_t *tokens_out, hipStream_t st);
 
