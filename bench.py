@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=4)
     ap.add_argument("--sample", type=float, default=0.0, metavar="T",
                     help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
+    ap.add_argument("--weight-swap", action="store_true",
+                    help="instead of decode steps, time re-packing a whole policy version (hx_weights_pack of every tensor, "
+                         "sources resident on the GPU) into the live engine")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this size (5 launches): the known traffic against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
@@ -154,6 +157,31 @@ def main():
     t_build = time.perf_counter() - t_build
     eng = dw.engine
     nbytes = dw.bytes()
+
+    if args.weight_swap:
+        # one layer's logical tensors serve as the source of every layer (the values do not matter for the timing)
+        src_layer = synth.layer_weights(s, 0, wl.seed + 1, device=torch.device("cuda"))
+        src_glob = synth.global_weights(s, wl.seed + 1, device=torch.device("cuda"))
+        torch.cuda.synchronize()
+
+        def swap():
+            for l in range(s.n_layers):
+                eng.pack_layer(l, src_layer)
+            eng.pack_globals(src_glob)
+
+        swap()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            swap()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 3
+        wbytes = s.weight_elements() * 2
+        print(json.dumps({"metric": "policy version swap: bf16 weights re-packed into the streaming layout", "value": wbytes / dt / 1e9,
+                          "unit": "GB/s of weights", "n_gpus": 1, "seconds_per_swap": dt, "weights_bytes": wbytes,
+                          "hbm_bytes_moved": 2 * wbytes, "decode_steps_equivalent": dt / 14.2e-3,
+                          "config": {"workload": wl.name, "model_shape": s.name}, "data": "synthetic", "dtype": "bf16"}))
+        return
 
     if args.sample > 0:
         s_tok = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")

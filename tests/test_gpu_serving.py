@@ -1,0 +1,177 @@
+"""What a rollout server does around the step, shown on the GPU through the C ABI: response groups sharing the
+physical blocks of their prompt, sequences leaving and joining between steps, and a new policy version packed
+into a live engine.  All of it rests on decode_step being a pure function of (weights, cache contents, inputs)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_00796_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+SHAPE = dataclasses.replace(synth.TINY, name="serving", n_layers=2)
+
+
+@pytest.fixture(scope="module")
+def hx():
+    from paper_2511_00796_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def engine_with(hx, seed, max_batch=16, max_seq_len=512):
+    eng = hx.Engine(SHAPE, max_batch, max_seq_len)
+    for l in range(SHAPE.n_layers):
+        eng.pack_layer(l, synth.layer_weights(SHAPE, l, seed))
+    eng.pack_globals(synth.global_weights(SHAPE, seed))
+    torch.cuda.synchronize()
+    return eng
+
+
+def step(eng, kv, tokens, ctx, table):
+    B = len(ctx)
+    logits = torch.empty(B, SHAPE.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(B, dtype=torch.int32, device="cuda")
+    ctx = np.asarray(ctx, dtype=np.int32)
+    eng.decode_step(kv, dev(np.asarray(tokens, np.int32)), dev(ctx), dev(ctx + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    return logits.cpu(), nxt.cpu()
+
+
+def test_response_groups_share_the_blocks_of_their_prompt(hx):
+    """2 prompts x 3 responses.  Prompt length 48 = 3 full blocks.  Layout A gives every sequence private copies of
+    its prompt's K/V; layout B maps the first three table entries of a group to the SAME physical blocks.  The step
+    reads the same values either way, so logits and tokens are identical bit for bit, with 12 fewer blocks."""
+    eng = engine_with(hx, 7)
+    P, resp = 48, [5, 17, 30, 1, 16, 33]
+    ctx = np.array([P + r for r in resp], dtype=np.int32)
+    nblk = (ctx + 1 + 15) // 16
+    rng = np.random.default_rng(11)
+    kvd = SHAPE.n_kv_heads * SHAPE.head_dim
+    total = int(ctx.sum())
+    start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
+    tokens = rng.integers(0, SHAPE.vocab, size=6)
+
+    def kv_data(layer):
+        k = rng.normal(0, 1, size=(total, kvd)).astype(np.float32)
+        v = rng.normal(0, 1, size=(total, kvd)).astype(np.float32)
+        for grp in range(2):                               # the prompt part is common to the group's sequences
+            first = 3 * grp
+            for b in range(first + 1, first + 3):
+                k[start[b]:start[b] + P] = k[start[first]:start[first] + P]
+                v[start[b]:start[b] + P] = v[start[first]:start[first] + P]
+        shp = (total, SHAPE.n_kv_heads, SHAPE.head_dim)
+        return torch.from_numpy(k).to(torch.bfloat16).reshape(shp), torch.from_numpy(v).to(torch.bfloat16).reshape(shp)
+
+    data = [kv_data(l) for l in range(SHAPE.n_layers)]
+    width = int(nblk.max())
+    # layout A: private blocks, shuffled
+    nA = int(nblk.sum())
+    permA = rng.permutation(nA)
+    tableA = np.full((6, width), -1, dtype=np.int32)
+    at = 0
+    for b in range(6):
+        tableA[b, :nblk[b]] = permA[at:at + nblk[b]]
+        at += nblk[b]
+    # layout B: blocks 0..2 of a group shared
+    nB = nA - 2 * 2 * 3
+    permB = list(rng.permutation(nB))
+    tableB = np.full((6, width), -1, dtype=np.int32)
+    for grp in range(2):
+        shared = [permB.pop() for _ in range(3)]
+        for b in range(3 * grp, 3 * grp + 3):
+            tableB[b, :3] = shared
+            tableB[b, 3:nblk[b]] = [permB.pop() for _ in range(nblk[b] - 3)]
+    assert not permB
+    outs = []
+    for table, n in ((tableA, nA), (tableB, nB)):
+        kv = hx.KVCache(eng, n)
+        kv.pool.zero_()
+        for l, (k, v) in enumerate(data):
+            kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table))
+        outs.append(step(eng, kv, tokens, ctx, table))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.isfinite(outs[0][0]).all()
+
+
+def test_sequences_leave_and_join_between_steps(hx):
+    """Step a batch of 6, then drop two sequences and admit a new one.  Every sequence's logits are those it gets
+    when it is stepped alone: up to fp32 summation order, which the attention schedule (cut points depend on the
+    whole batch) and the m-group of the products may change -- so tolerance, not equality; tokens must agree."""
+    eng = engine_with(hx, 8)
+    rng = np.random.default_rng(12)
+    ctx_all = np.array([40, 300, 17, 129, 255, 64, 90], dtype=np.int32)
+    nblk = (ctx_all + 1 + 15) // 16
+    width = int(nblk.max())
+    n = int(nblk.sum())
+    perm = rng.permutation(n)
+    table_all = np.full((7, width), -1, dtype=np.int32)
+    at = 0
+    for b in range(7):
+        table_all[b, :nblk[b]] = perm[at:at + nblk[b]]
+        at += nblk[b]
+    start = np.concatenate([[0], np.cumsum(ctx_all)]).astype(np.int32)
+    kv = hx.KVCache(eng, n)
+    kv.pool.zero_()
+    for l in range(SHAPE.n_layers):
+        k, v = synth.kv_fill(SHAPE, l, int(ctx_all.sum()), 99)
+        kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table_all))
+    tokens_all = rng.integers(0, SHAPE.vocab, size=7)
+
+    def run(rows):
+        rows = list(rows)
+        return step(eng, kv, tokens_all[rows], ctx_all[rows], table_all[rows])
+
+    alone = [run([b]) for b in range(7)]        # each step re-writes the same K/V at position ctx: idempotent
+    first = run(range(6))
+    second = run([0, 2, 3, 5, 6])
+    for rows, (logits, nxt) in ((list(range(6)), first), ([0, 2, 3, 5, 6], second)):
+        for i, b in enumerate(rows):
+            ref = alone[b][0][0]
+            scale = float(ref.abs().max())
+            assert float((logits[i] - ref).abs().max()) <= 1e-3 * scale, (b, float((logits[i] - ref).abs().max()), scale)
+            assert int(nxt[i]) == int(alone[b][1][0])
+
+
+def test_new_policy_version_packed_into_a_live_engine(hx):
+    """hx_weights_pack overwrites the streaming-layout weights in place: after packing version B the engine is
+    indistinguishable (bit for bit) from one created with B, and packing A again restores A's outputs."""
+    rng = np.random.default_rng(13)
+    ctx = np.array([33, 100, 7], dtype=np.int32)
+    nblk = (ctx + 1 + 15) // 16
+    table, n = synth.block_table(ctx + 1, 16, 3)
+    start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
+    tokens = rng.integers(0, SHAPE.vocab, size=3)
+
+    def cache_for(eng):
+        kv = hx.KVCache(eng, n)
+        kv.pool.zero_()
+        for l in range(SHAPE.n_layers):
+            k, v = synth.kv_fill(SHAPE, l, int(ctx.sum()), 5)
+            kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table))
+        return kv
+
+    def pack(eng, seed):
+        for l in range(SHAPE.n_layers):
+            eng.pack_layer(l, synth.layer_weights(SHAPE, l, seed))
+        eng.pack_globals(synth.global_weights(SHAPE, seed))
+        torch.cuda.synchronize()
+
+    live = engine_with(hx, 21)
+    out_a = step(live, cache_for(live), tokens, ctx, table)
+    fresh_b = engine_with(hx, 22)
+    out_b = step(fresh_b, cache_for(fresh_b), tokens, ctx, table)
+    assert not torch.equal(out_a[0], out_b[0])
+    pack(live, 22)
+    swapped = step(live, cache_for(live), tokens, ctx, table)
+    assert torch.equal(swapped[0], out_b[0]) and torch.equal(swapped[1], out_b[1])
+    pack(live, 21)
+    back = step(live, cache_for(live), tokens, ctx, table)
+    assert torch.equal(back[0], out_a[0])
