@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32)
-    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--sample", type=float, default=0.0, metavar="T",
                     help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
     ap.add_argument("--weight-swap", action="store_true",
