@@ -191,6 +191,13 @@ int hx_stage_schedule(hx_engine *engine, int32_t batch, const int32_t *seq_lens,
                       int32_t *sched_out, void *stream);
 int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention kernel */
 
+/* How a matrix product of n_tiles 32-column tiles and k_steps 16-row steps is launched for `batch` rows (host logic
+   only, no GPU work): tiles per workgroup, k-slices per workgroup, and K-splits whose fp32 partial results the consumer
+   kernel adds (only if `partial` != 0; products with a fused epilogue are never split).  HX_E_RANGE for sizes < 1 or
+   batch > 256, HX_E_NULL for NULL outputs. */
+int hx_plan_product(int32_t n_tiles, int32_t k_steps, int32_t batch, int32_t partial, int32_t *tiles_per_workgroup_out,
+                    int32_t *k_slices_out, int32_t *splits_out);
+
 /* bias + RoPE + cache append of one layer: qkv_dev fp32 [batch, qkv_cols] is the projection WITHOUT
    bias (the packed bias of `layer` is added); writes K/V of position positions[b] into `kv` and
    returns the rotated, bf16-rounded query as fp32 in q_out_dev [batch, n_q_heads * head_dim]. */

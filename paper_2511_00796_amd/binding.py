@@ -21,7 +21,7 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "decode_step_sample", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves",
+           "decode_step", "decode_step_sample", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
            "hx_profile_enable", "hx_profile_read"]
 
@@ -75,6 +75,7 @@ def load():
         "hx_set_attn_capture": [vp, vp],
         "hx_stage_schedule": [vp, i32, vp, vp, vp, vp],
         "hx_attention_waves": [vp],
+        "hx_plan_product": [i32, i32, i32, i32, vp, vp, vp],
         "hx_stage_rope_append": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_attention": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],

@@ -485,6 +485,17 @@ static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_lau
     return 1;
 }
 
+// The plan of one product, for inspection: tiles per workgroup, k-slices per workgroup, K-splits.
+extern "C" int hx_plan_product(int32_t n_tiles, int32_t k_steps, int32_t batch, int32_t partial, int32_t *wn_out,
+                               int32_t *wk_out, int32_t *splits_out) {
+    if (!wn_out || !wk_out || !splits_out) return hx_fail(HX_E_NULL, "an output pointer is NULL");
+    if (n_tiles < 1 || k_steps < 1 || batch < 1 || batch > 256) return hx_fail(HX_E_RANGE, "product %d x %d for batch %d", n_tiles, k_steps, batch);
+    gemm_launch plan[2];
+    plan_product(n_tiles, k_steps, hx_m_groups(batch), partial != 0, plan);
+    *wn_out = plan[0].wn; *wk_out = plan[0].wk; *splits_out = plan[0].splits;
+    return HX_OK;
+}
+
 int hx_gemm_splits(const hx_matrix *m, int batch) {
     gemm_launch plan[2];
     plan_product(m->n_tiles, m->k_steps, hx_m_groups(batch), true, plan);

@@ -92,9 +92,46 @@ def test_engine_create_validates_buffers_on_the_host():
     assert lib.decode_step(eng, kvh, 4, p, p, p, p, 0, None, p, None) == binding.HX_E_RANGE
     assert lib.decode_step(eng, kvh, 4, None, p, p, p, 4, None, p, None) == binding.HX_E_NULL
     assert lib.decode_step(None, kvh, 4, p, p, p, p, 4, None, p, None) == binding.HX_E_NULL
+    f32 = C.c_float
+    assert lib.decode_step_sample(eng, kvh, 4, p, p, p, p, 4, f32(0.0), 1, None, None, p, p, None) == binding.HX_E_RANGE
+    assert lib.decode_step_sample(eng, kvh, 4, p, p, p, p, 4, f32(-2.0), 1, None, None, p, p, None) == binding.HX_E_RANGE
+    assert lib.decode_step_sample(eng, kvh, 4, p, p, p, p, 4, f32(float("nan")), 1, None, None, p, p, None) == binding.HX_E_RANGE
+    assert lib.decode_step_sample(eng, kvh, 4, p, p, p, p, 4, f32(1.0), 1, None, None, p, None, None) == binding.HX_E_NULL
+    assert lib.decode_step_sample(eng, kvh, 9, p, p, p, p, 4, f32(1.0), 1, None, None, p, p, None) == binding.HX_E_RANGE
     assert lib.hx_weights_pack(eng, binding.HX_T_WO, 0, p, 3, 3, None) == binding.HX_E_SHAPE
     assert lib.hx_weights_pack(eng, binding.HX_T_WO, 9, p, 256, 256, None) == binding.HX_E_SHAPE
     assert lib.hx_weights_pack(eng, 99, 0, p, 256, 256, None) == binding.HX_E_SHAPE
     assert lib.kv_free(kvh) == binding.HX_OK
     assert lib.hx_engine_destroy(eng) == binding.HX_OK
     assert lib.hx_engine_destroy(None) == binding.HX_E_NULL
+
+
+def test_product_plans_fill_the_chip_and_respect_their_limits():
+    """Host-side launch planner: every plan keeps at least 16 k-steps per split, never splits a product whose epilogue
+    needs the whole sum, stays within 9 splits and 4..6 tiles per workgroup, and for the 7B shapes picks the plans the
+    design rests on (gate|up: 237 workgroups of 5 = one round on 256 compute units; O and QKV: 7 splits of exactly two
+    ring revolutions; down: 9 splits)."""
+    lib = binding.load()
+
+    def plan(n_tiles, k_steps, batch, partial):
+        wn, wk, sp = C.c_int32(), C.c_int32(), C.c_int32()
+        assert lib.hx_plan_product(n_tiles, k_steps, batch, int(partial), C.byref(wn), C.byref(wk), C.byref(sp)) == binding.HX_OK
+        return wn.value, wk.value, sp.value
+
+    for s in (synth.TINY, synth.QWEN_1P5B, synth.QWEN_7B, synth.QWEN_14B):
+        for K, N, partial in ((s.hidden, s.qkv_dim, True), (s.q_dim, s.hidden, True), (s.hidden, 2 * s.intermediate, False),
+                              (s.intermediate, s.hidden, True), (s.hidden, s.vocab, False)):
+            for batch in (1, 4, 64, 128, 256):
+                wn, wk, sp = plan((N + 31) // 32, K // 16, batch, partial)
+                assert 4 <= wn <= 6 and wk == 1 and 1 <= sp <= 9
+                assert sp == 1 or (K // 16) // sp >= 16
+                assert partial or sp == 1
+    s = synth.QWEN_7B
+    assert plan(2 * s.intermediate // 32, s.hidden // 16, 128, False) == (5, 1, 1)
+    assert plan(s.hidden // 32, s.q_dim // 16, 128, True) == (4, 1, 7)
+    assert plan(s.qkv_dim // 32, s.hidden // 16, 128, True) == (4, 1, 7)
+    assert plan(s.hidden // 32, s.intermediate // 16, 128, True) == (4, 1, 9)
+    none = C.c_int32()
+    assert lib.hx_plan_product(0, 10, 4, 1, C.byref(none), C.byref(none), C.byref(none)) == binding.HX_E_RANGE
+    assert lib.hx_plan_product(10, 10, 300, 1, C.byref(none), C.byref(none), C.byref(none)) == binding.HX_E_RANGE
+    assert lib.hx_plan_product(10, 10, 4, 1, None, C.byref(none), C.byref(none)) == binding.HX_E_NULL
