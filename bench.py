@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--sample", type=float, default=0.0, metavar="T",
                     help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
+    ap.add_argument("--prefill", type=int, default=0, metavar="P",
+                    help="instead of decode steps, time prompt processing: 128 prompts of P tokens through prefill_chunk, "
+                         "256 token rows per call (reported as prompt tokens/s)")
     ap.add_argument("--weight-swap", action="store_true",
                     help="instead of decode steps, time re-packing a whole policy version (hx_weights_pack of every tensor, "
                          "sources resident on the GPU) into the live engine")
@@ -150,6 +153,41 @@ def main():
                             [synth.as_u16(t[name][seq_start[r]: seq_start[r] + ctx[r]]) for r in rows]))
     else:
         tap = None
+
+    if args.prefill:
+        P, B, R = args.prefill, 128, 256
+        eng = binding.Engine(s, R, P + 1)
+        for l in range(s.n_layers):
+            eng.pack_layer(l, synth.layer_weights(s, l, wl.seed, device=torch.device("cuda")))
+        eng.pack_globals(synth.global_weights(s, wl.seed, device=torch.device("cuda")))
+        lens = np.full(B, P + 1, dtype=np.int32)
+        table, nb = synth.block_table(lens, s.block_size, wl.seed)
+        kvc = binding.KVCache(eng, nb)
+        kvc.pool.zero_()
+        per_seq = R // B                                     # positions of each sequence per call
+        seq_of_row = torch.arange(R, device="cuda") // per_seq
+        off_of_row = (torch.arange(R, device="cuda") % per_seq).to(torch.int32)
+        table_rows = torch.from_numpy(table).cuda()[seq_of_row].contiguous()
+        toks = torch.randint(0, s.vocab, (R,), dtype=torch.int32, device="cuda")
+        calls = P // per_seq
+
+        def run():
+            for c in range(calls):
+                pos = off_of_row + c * per_seq
+                eng.prefill_chunk(kvc, toks, pos, pos + 1, table_rows)
+
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print(json.dumps({"metric": "prompt tokens/s through prefill_chunk (rows = prompt tokens, decode-style attention)",
+                          "value": B * calls * per_seq / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
+                          "rows_per_call": R, "ms_per_call": dt / calls * 1e3,
+                          "config": {"workload": "%s-prefill" % s.name, "prompts": B, "prompt_len": P}, "data": "synthetic",
+                          "dtype": "bf16"}))
+        return
 
     t_build = time.perf_counter()
     dw = workload.build(wl, tap=tap)

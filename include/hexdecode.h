@@ -176,6 +176,17 @@ int decode_step_sample(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_
                        int32_t max_blocks_per_seq, float temperature, uint64_t seed, const int32_t *row_ids,
                        float *logits_out, int32_t *tokens_out, float *logprobs_out, void *stream);
 
+/* Prompt processing in chunks: the step for n_rows (<= max_batch) PROMPT TOKENS at once, without LM head -- only the
+   K and V of every row enter the cache (rollouts start from a prompt: paper Section 1, stage (i); Section 4.2.2).
+   A row is one token of one sequence: tokens[r] at positions[r], attending seq_lens[r] = positions[r] + 1 keys
+   through block_table row r -- rows of the same sequence carry copies of that sequence's table row.  Rows of one
+   sequence in one call must cover consecutive positions that continue its cache (K and V of all rows are written
+   before any row attends, so a row sees the rows before it); chunks of a sequence are submitted in position order.
+   The last prompt token is then given to decode_step / decode_step_sample, which yields the first generated token.
+   Arguments, ownership and errors as decode_step. */
+int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
+                  const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
+
 /* Parity hook: when attn_dev is not NULL every following decode_step also writes the attention
    output of every layer BEFORE its bf16 rounding to attn_dev, DEVICE fp32
    [n_layers, batch, n_q_heads * head_dim] (batch = that step's batch).  NULL switches it off. */

@@ -21,7 +21,7 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "decode_step_sample", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
+           "decode_step", "decode_step_sample", "prefill_chunk", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
            "hx_profile_enable", "hx_profile_read"]
 
@@ -71,6 +71,7 @@ def load():
         "prefill_fill": [vp, C.c_int, vp, vp, vp, vp, i32, i32, i64, vp],
         "hx_kv_gather": [vp, C.c_int, vp, vp, vp, vp, i32, i32, i64, vp],
         "decode_step": [vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp],
+        "prefill_chunk": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
         "decode_step_sample": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "hx_set_attn_capture": [vp, vp],
         "hx_stage_schedule": [vp, i32, vp, vp, vp, vp],
@@ -180,6 +181,11 @@ class Engine:
         B = tokens.numel()
         _check(load().decode_step(self.handle, kv.handle, B, _ptr(tokens), _ptr(positions), _ptr(seq_lens),
                                   _ptr(block_table), block_table.shape[1], _ptr(logits), _ptr(next_tokens), _stream()))
+
+    def prefill_chunk(self, kv: "KVCache", tokens, positions, seq_lens, block_table) -> None:
+        """Rows = prompt tokens (<= max_batch); block_table holds one table row per ROW."""
+        _check(load().prefill_chunk(self.handle, kv.handle, tokens.numel(), _ptr(tokens), _ptr(positions), _ptr(seq_lens),
+                                    _ptr(block_table), block_table.shape[1], _stream()))
 
     def decode_step_sample(self, kv: "KVCache", tokens, positions, seq_lens, block_table, temperature: float, seed: int,
                            logits: Optional[torch.Tensor], out_tokens: torch.Tensor, out_logprobs: torch.Tensor,

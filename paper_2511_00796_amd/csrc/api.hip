@@ -381,11 +381,12 @@ static int check_step_args(const hx_engine *e, const hx_kv *kv, int32_t batch, i
 
 static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
                     const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
-                    int32_t *next_tokens_out, float *logprobs_out, const hx_sample_params *sample, void *stream) {
+                    int32_t *next_tokens_out, float *logprobs_out, const hx_sample_params *sample, bool with_head,
+                    void *stream) {
     int rc = check_step_args(e, kv, batch, max_blocks);
     if (rc) return rc;
     if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
-    if (!tokens || !positions || !seq_lens || !block_table || !next_tokens_out)
+    if (!tokens || !positions || !seq_lens || !block_table || (with_head && !next_tokens_out))
         return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
     hipStream_t st = (hipStream_t)stream;
     const hx_model_config *c = &e->cfg;
@@ -400,6 +401,7 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
         HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st));
         HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, hx_gemm_splits(&lm->wqkv, batch), (size_t)batch * e->qkv_dim,
                                                  positions, block_table, max_blocks, st));
+        if (!with_head && l + 1 == c->n_layers) break;   // prompt rows: of the last layer only its K and V are needed
         HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
         HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st));
         HX_TIMED(HX_K_GEMM_O, hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st));
@@ -409,6 +411,7 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
         const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wd, batch), (size_t)batch * c->hidden, next_gain, st));
     }
+    if (!with_head) return HX_OK;
     if (sample) {
         HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_SAMPLE, logits_out, nullptr, st, sample));
         HX_TIMED(HX_K_SETUP, hx_launch_sample_final(e, batch, next_tokens_out, logprobs_out, st));
@@ -423,7 +426,13 @@ extern "C" int decode_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t
                            const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, float *logits_out,
                            int32_t *next_tokens_out, void *stream) {
     return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, next_tokens_out,
-                    nullptr, nullptr, stream);
+                    nullptr, nullptr, true, stream);
+}
+
+extern "C" int prefill_chunk(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
+                             const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, void *stream) {
+    return run_step(e, kv, n_rows, tokens, positions, seq_lens, block_table, max_blocks, nullptr, nullptr, nullptr, nullptr,
+                    false, stream);
 }
 
 extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
@@ -440,7 +449,7 @@ extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const 
     sp.key0 = (uint32_t)seed;
     sp.key1 = (uint32_t)(seed >> 32);
     return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, tokens_out,
-                    logprobs_out, &sp, stream);
+                    logprobs_out, &sp, true, stream);
 }
 
 // ---- single stages ---------------------------------------------------------------------------------------------------

@@ -121,6 +121,68 @@ def test_tiny_config_prompt_then_16_greedy_steps(hx):
     assert np.mean(agree) >= 0.995
 
 
+def test_chunked_prompt_processing_matches_dense_causal_recomputation(hx):
+    """Config-1 model and prompts (32..128 tokens, batch 4).  All prompt tokens but the last go through
+    prefill_chunk, 48 rows per call with the four sequences interleaved (a row = one token; rows of a sequence carry
+    copies of its table row); the last prompt token goes through decode_step.  Its logits must equal the oracle's
+    DENSE causal recomputation of the whole prompt (no cache, no paging) within the contract bars, and four further
+    teacher-forced greedy steps on the cache that the chunks built must agree with the oracle's stepwise decode."""
+    wl = synth.WORKLOADS["tiny-b4"]
+    s = wl.shape
+    ow, g, layers = host_model(s, wl.seed)
+    cfg = oracle.make_config(s)
+    ctx = synth.context_lengths(wl)
+    final = ctx + 5
+    table, nb = synth.block_table(final, s.block_size, wl.seed)
+    prompts = [synth.token_ids(wl, int(ctx[b]), salt=b) for b in range(wl.batch)]
+    eng = hx.Engine(s, 48, int(final.max()))
+    for l in range(s.n_layers):
+        eng.pack_layer(l, synth.layer_weights(s, l, wl.seed))
+    eng.pack_globals(synth.global_weights(s, wl.seed))
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)                                        # NaN patterns wherever nothing is written
+    rows = [(b, p) for p in range(int(ctx.max())) for b in range(wl.batch) if p < ctx[b] - 1]
+    for at in range(0, len(rows), 48):
+        chunk = rows[at:at + 48]
+        bs = np.array([b for b, _ in chunk])
+        ps = np.array([p for _, p in chunk], dtype=np.int32)
+        toks = np.array([prompts[b][p] for b, p in chunk], dtype=np.int32)
+        eng.prefill_chunk(kv, dev(toks), dev(ps), dev(ps + 1), dev(table[bs]))
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[b][-1] for b in range(wl.batch)], dtype=np.int32)
+    logits = torch.empty(wl.batch, s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(wl.batch, dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    worst = 0.0
+    first = np.zeros(wl.batch, dtype=np.int32)
+    for b in range(wl.batch):
+        ref = oracle.full_causal(cfg, ow, prompts[b])[0][-1]
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(gl[b] - ref).max())
+        assert err <= LOGIT_TOL * scale, (b, err, scale)
+        worst = max(worst, err / scale)
+        first[b] = int(np.argmax(ref))
+        assert int(nxt[b]) == first[b] or np.sort(ref)[-1] - np.sort(ref)[-2] < 4 * err
+    # the oracle's own cache, built position by position, for the steps that follow
+    okv = oracle.PagedKV(cfg, nb)
+    for p in range(int(ctx.max())):
+        rr = [b for b in range(wl.batch) if p < ctx[b]]
+        oracle.decode_step(cfg, ow, okv, np.array([prompts[b][p] for b in rr]), np.full(len(rr), p), np.full(len(rr), p + 1), table[rr])
+    cur, pos = first.copy(), ctx.astype(np.int64).copy()
+    for step in range(4):
+        eng.decode_step(kv, dev(cur.astype(np.int32)), dev(pos.astype(np.int32)), dev((pos + 1).astype(np.int32)), dev(table), logits, nxt)
+        torch.cuda.synchronize()
+        rl, rn = oracle.decode_step(cfg, ow, okv, cur, pos, pos + 1, table)[:2]
+        scale = float(np.abs(rl).max())
+        err = float(np.abs(logits.cpu().numpy() - rl).max())
+        assert err <= LOGIT_TOL * scale, (step, err, scale)
+        worst = max(worst, err / scale)
+        cur, pos = rn, pos + 1
+    print("chunked prompt processing: worst logit err / max|logit| %.3e" % worst)
+
+
 def test_decode_step_is_deterministic_and_tokens_are_argmax_of_logits(hx):
     from paper_2511_00796_amd import workload
     wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=48, lo=100, hi=3000)
