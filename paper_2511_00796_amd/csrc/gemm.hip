@@ -57,13 +57,11 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 // the end.  Every consumer keeps RING weight loads (1 KiB each, non-temporal) in flight in a register ring
 // and issues no other vector-memory load, so the in-order load counter never makes it wait for anything but
 // the tile it is about to use.  Producers copy the activations of the coming chunks (KC k-steps of every
-// k-slice, 32 KiB per stage) from L2 straight into a four-stage LDS buffer; one workgroup barrier per chunk
-// hands a stage over.  With up to 96 KiB of activations in flight per compute unit the copy keeps pace with
-// the weight stream at HBM speed.
+// k-slice, 32 KiB per stage) from L2 straight into a four-stage LDS buffer (two stages of 64 KiB for 8 m-groups);
+// one workgroup barrier per chunk hands a stage over.
 #ifndef HX_GEMM_RING
 #define HX_GEMM_RING 16
 #endif
-#define HX_GEMM_NBUF 4
 
 struct GemmArgs {
     const uint4 *wp;      // packed weights
@@ -105,7 +103,10 @@ __device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 template <int MG, int WK> struct GemmGeom {
-    static constexpr int KC0 = 32 / (WK * MG);
+    // stages: 4 x 32 KiB; with 8 m-groups 2 x 64 KiB, so that a stage still holds 8 k-steps (one barrier per 8)
+    static constexpr int NBUF = MG >= 8 ? 2 : 4;
+    static constexpr int STAGE_KB = MG >= 8 ? 64 : 32;
+    static constexpr int KC0 = STAGE_KB / (WK * MG);
     static constexpr int KC = KC0 > 8 ? 8 : (KC0 < 1 ? 1 : KC0);   // k-steps per LDS chunk
     static constexpr int SLICE_U4 = KC * MG * 64;                   // uint4 per k-slice per stage
     static constexpr int PVT = WK * KC * MG;                        // 1-KiB copies per stage
@@ -114,7 +115,7 @@ template <int MG, int WK> struct GemmGeom {
     static constexpr int STAGE_BYTES = WK * SLICE_U4 * 16;
 };
 template <int MG, int WN, int WK> constexpr int gemm_lds_bytes() {
-    constexpr int stages = HX_GEMM_NBUF * GemmGeom<MG, WK>::STAGE_BYTES;
+    constexpr int stages = GemmGeom<MG, WK>::NBUF * GemmGeom<MG, WK>::STAGE_BYTES;
     constexpr int red = (WK - 1) * WN * MG * 4096;
     return stages > red ? stages : red;
 }
@@ -127,12 +128,12 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
     const int32_t *__restrict__ a_positions, const int32_t *__restrict__ a_row_ids, float a_inv_t, uint32_t a_key0,
     uint32_t a_key1, float *__restrict__ a_samp_z, float *__restrict__ a_samp_m, float *__restrict__ a_samp_s) {
     using GG = GemmGeom<MG, WK>;
-    constexpr int RING = HX_GEMM_RING, NBUF = HX_GEMM_NBUF;
+    constexpr int RING = HX_GEMM_RING, NBUF = GG::NBUF, LOOK = NBUF - 1;
     constexpr int KC = GG::KC, CPR = RING / KC, SLICE_U4 = GG::SLICE_U4, NC = WN * WK;
     // with at most 8 wavefronts per workgroup each may use 256 registers: enough to read B operands ahead
     constexpr bool PREFETCH_B = (NC + GG::NP <= 8) && MG <= 4;
     static_assert(RING % KC == 0, "ring must hold whole chunks");
-    static_assert(2 * GG::PVP <= 63, "two stages of copies must fit the load counter");
+    static_assert(LOOK * GG::PVP <= 63, "the stages in flight must fit the load counter");
     extern __shared__ u32x4_t xs[];                      // [NBUF][WK][SLICE_U4]
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -172,15 +173,14 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
             }
         };
         const int n_virtual = n_chunks + CPR;
-        copy_chunk(0);
-        copy_chunk(1);
-        copy_chunk(2);
-        __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * GG::PVP));   // stage 0 has landed
+#pragma unroll
+        for (int q = 0; q < LOOK; ++q) copy_chunk(q);
+        __builtin_amdgcn_s_waitcnt(HX_VMCNT((LOOK - 1) * GG::PVP));   // stage 0 has landed
         __syncthreads();
         for (int v = 0; v < n_virtual; ++v) {
-            if (v + 3 < n_virtual) {
-                copy_chunk(v + 3);                            // into the stage the consumers left at the last barrier
-                __builtin_amdgcn_s_waitcnt(HX_VMCNT(2 * GG::PVP)); // stage v + 1 has landed
+            if (v + LOOK < n_virtual) {
+                copy_chunk(v + LOOK);                            // into the stage the consumers left at the last barrier
+                __builtin_amdgcn_s_waitcnt(HX_VMCNT((LOOK - 1) * GG::PVP)); // stage v + 1 has landed
             } else {
                 __builtin_amdgcn_s_waitcnt(HX_VMCNT(0));      // nothing is in flight once the loop ends
             }
@@ -243,15 +243,23 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                     }
                 }
             } else {
+                // too many accumulators to hold two steps of B operands: read them DEPTH operands ahead of the
+                // multiply that uses them, in the order (k-step, m-group) in which the stage stores them
+                constexpr int DEPTH = 3, ITEMS = KC * MG;
+                u32x4_t bq[DEPTH];
+#pragma unroll
+                for (int t = 0; t < DEPTH; ++t) bq[t] = xb[t * 64];
 #pragma unroll
                 for (int j = 0; j < KC; ++j) {
                     const int s = c * KC + j;
-                    if (s < n_valid) {
-                        const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
+                    const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
 #pragma unroll
-                        for (int g = 0; g < MG; ++g)
-                            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                aop, __builtin_bit_cast(bf16x8_t, xb[(j * MG + g) * 64]), acc[g], 0, 0, 0);
+                    for (int g = 0; g < MG; ++g) {
+                        const int t = j * MG + g;
+                        const u32x4_t bcur = bq[t % DEPTH];
+                        if (t + DEPTH < ITEMS) bq[t % DEPTH] = xb[(t + DEPTH) * 64];
+                        if (s < n_valid)
+                            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, __builtin_bit_cast(bf16x8_t, bcur), acc[g], 0, 0, 0);
                     }
                     ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
                 }
