@@ -132,6 +132,8 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
     constexpr int KC = GG::KC, CPR = RING / KC, SLICE_U4 = GG::SLICE_U4, NC = WN * WK;
     // with at most 8 wavefronts per workgroup each may use 256 registers: enough to read B operands ahead
     constexpr bool PREFETCH_B = (NC + GG::NP <= 8) && MG <= 4;
+    // activations staged through producer registers (two sets of PVP x 16 bytes per lane) where those fit
+    constexpr bool COPY_VIA_REGISTERS = GG::PVP <= 16;
     static_assert(RING % KC == 0, "ring must hold whole chunks");
     static_assert(LOOK * GG::PVP <= 63, "the stages in flight must fit the load counter");
     extern __shared__ u32x4_t xs[];                      // [NBUF][WK][SLICE_U4]
@@ -173,6 +175,47 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
             }
         };
         const int n_virtual = n_chunks + CPR;
+        if constexpr (COPY_VIA_REGISTERS) {
+        // The copy goes through registers (global load, then LDS store): measured faster than the direct L2 -> LDS
+        // path, which slows the weight stream of the same compute unit down when both run (timing lab: weights alone
+        // 27 us, direct copy alone 18 us, both 49 us for 60 workgroups).
+        // Chunk v + 2 is requested while chunk v + 1 is stored; n_virtual is even, so the two register sets alternate
+        // statically.  Stage v + 1 is written between the barriers that end chunks v - 1 and v; the buffer it replaces
+        // (chunk v + 1 - NBUF) was released at or before the first of them.
+        static_assert(!COPY_VIA_REGISTERS || (RING / KC) % 2 == 0, "register sets alternate in pairs of chunks");
+        u32x4_t ra[GG::PVP], rb[GG::PVP];
+        auto load_chunk = [&](int v, u32x4_t (&r)[GG::PVP]) {
+            const int c = max(v - CPR, 0);
+#pragma unroll
+            for (int f = 0; f < GG::PVP; ++f) {
+                const int ff = pid * GG::PVP + f;
+                const int w = ff / (KC * MG), i = ff % (KC * MG);
+                const int kb = min(split1, split0 + w * a_steps_per_wave);
+                r[f] = xp4[min((kb + c * KC) * MG * 64 + i * 64 + lane, last_u4)];
+            }
+        };
+        auto store_chunk = [&](int v, const u32x4_t (&r)[GG::PVP]) {
+            const int buf = v % NBUF;
+#pragma unroll
+            for (int f = 0; f < GG::PVP; ++f) {
+                const int ff = pid * GG::PVP + f;
+                const int w = ff / (KC * MG), i = ff % (KC * MG);
+                xs[(buf * WK + w) * SLICE_U4 + i * 64 + lane] = r[f];
+            }
+        };
+        load_chunk(0, ra);
+        load_chunk(1, rb);
+        store_chunk(0, ra);
+        __syncthreads();
+        for (int v = 0; v < n_virtual; v += 2) {
+            if (v + 2 < n_virtual) load_chunk(v + 2, ra);
+            store_chunk(v + 1, rb);
+            __syncthreads();
+            if (v + 3 < n_virtual) load_chunk(v + 3, rb);
+            if (v + 2 < n_virtual) store_chunk(v + 2, ra);
+            __syncthreads();
+        }
+        } else {
 #pragma unroll
         for (int q = 0; q < LOOK; ++q) copy_chunk(q);
         __builtin_amdgcn_s_waitcnt(HX_VMCNT((LOOK - 1) * GG::PVP));   // stage 0 has landed
@@ -185,6 +228,7 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                 __builtin_amdgcn_s_waitcnt(HX_VMCNT(0));      // nothing is in flight once the loop ends
             }
             __syncthreads();
+        }
         }
         if (WK > 1) __syncthreads();
         return;
