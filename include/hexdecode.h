@@ -202,6 +202,12 @@ int hx_stage_schedule(hx_engine *engine, int32_t batch, const int32_t *seq_lens,
                       int32_t *sched_out, void *stream);
 int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention kernel */
 
+/* Tuning knobs read from the environment (none is needed for correct or fast operation; results stay within the
+   same tolerances, only summation order changes):
+     HX_ATTN_WAVES=n        wavefronts of the attention kernel, read at hx_engine_create (default 2048 = 8 per CU)
+     HX_GEMM_SHAPE=wn,wk,s  force tiles per workgroup (4..6, or 4 with wk = 2), k-slices per workgroup and K-splits
+     HX_GEMM_MAX_SPLITS=s   upper bound of the planner's K-splits (1..9)                                            */
+
 /* How a matrix product of n_tiles 32-column tiles and k_steps 16-row steps is launched for `batch` rows (host logic
    only, no GPU work): tiles per workgroup, k-slices per workgroup, and K-splits whose fp32 partial results the consumer
    kernel adds (only if `partial` != 0; products with a fused epilogue are never split).  HX_E_RANGE for sizes < 1 or

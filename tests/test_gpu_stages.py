@@ -179,6 +179,20 @@ def test_linear_stages_match_oracle(hx, name, batch):
     """Every matrix product of the layer and the LM head: bf16 inputs, fp32 accumulation.  The GPU sums
     in matrix-core / split order, the oracle in ascending k, so values agree to fp32 reassociation:
     |err| <= 1e-5 * sum_k |x_k w_kn| (K <= 1376 here); measured ~1e-6."""
+    linear_checks(hx, name, batch)
+
+
+@pytest.mark.parametrize("plan", ["4,2,1", "4,2,2", "5,1,2", "6,1,3", "4,1,5"])
+def test_linear_stages_under_every_launch_shape(hx, plan, monkeypatch):
+    """The planner normally picks tiles per workgroup, k-slices per workgroup and K-splits; HX_GEMM_SHAPE forces
+    them, so the shapes it does not pick for these small matrices (two k-slices summed through LDS, 5 and 6 tiles
+    per workgroup, several splits) are checked against the oracle too."""
+    monkeypatch.setenv("HX_GEMM_SHAPE", plan)
+    linear_checks(hx, "d128_g7", 70)
+    linear_checks(hx, "d128_g1", 130)
+
+
+def linear_checks(hx, name, batch):
     shape = STAGE_SHAPES[name]
     eng = build_engine(hx, shape, 4, max(batch, 8), 64)
     _, g, layers = host_model(shape, 4)
