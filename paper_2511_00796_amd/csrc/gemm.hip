@@ -3,13 +3,13 @@
 // The weights dominate the bytes, so the kernel is organised around streaming each packed weight
 // tile exactly once, straight from HBM into the A operand of v_mfma_f32_32x32x16_bf16 (32 output
 // columns n x 16 k per 1-KiB load).  The activations are the B operand (16 k x 32 batch rows per
-// m-group); they are small, L2-resident, and shared by the four wavefronts of a workgroup through
-// a double-buffered LDS copy.  Each wavefront owns one 32-column n-tile and all batch rows, so the
+// m-group); they are small, L2-resident, and shared by the consumer wavefronts of a workgroup through
+// a multi-stage LDS copy made by dedicated producer wavefronts.  Each wavefront owns one 32-column n-tile and all batch rows, so the
 // accumulator is MG tiles of 32 x 32 fp32.  Along K the product may be split over workgroups; the
 // fp32 partial results are summed in split order by the consumer kernel (deterministic).
 //
 // Epilogues: plain fp32 partials; SiLU(gate) * up -> bf16 packed activations of the down
-// projection; logits + per-tile argmax candidates.
+// projection; logits + per-tile argmax candidates; logits + per-tile sampling candidates and log-sum-exp pieces.
 #include "hx_internal.h"
 #include <algorithm>
 
@@ -56,9 +56,10 @@ int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *sr
 // Consumers: WN adjacent n-tiles, each split into WK k-slices that are summed in slice order through LDS at
 // the end.  Every consumer keeps RING weight loads (1 KiB each, non-temporal) in flight in a register ring
 // and issues no other vector-memory load, so the in-order load counter never makes it wait for anything but
-// the tile it is about to use.  Producers copy the activations of the coming chunks (KC k-steps of every
-// k-slice, 32 KiB per stage) from L2 straight into a four-stage LDS buffer (two stages of 64 KiB for 8 m-groups);
-// one workgroup barrier per chunk hands a stage over.
+// the tile it is about to use.  Producers stage the activations of the coming chunks (KC k-steps of every
+// k-slice, 32 KiB per stage, four stages; two stages of 64 KiB for 8 m-groups) in LDS: through their own
+// registers where two chunks fit them, else with the direct L2 -> LDS load; one workgroup barrier per chunk
+// hands a stage over.
 #ifndef HX_GEMM_RING
 #define HX_GEMM_RING 16
 #endif
@@ -153,10 +154,9 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
 
     if (producer) {
         // k-slice w of this workgroup covers k-steps [split0 + w*spw, min(split1, +spw)); chunk c of it is a
-        // contiguous run of the packed activations, copied L2 -> LDS without passing through registers.
+        // contiguous run of the packed activations.
         // Virtual chunk v is real chunk max(v - CPR, 0): the consumers spend their first ring revolution
         // multiplying zeros (ring not filled yet) with chunk 0, then fall into step with the real chunks.
-        // Stages v+1 .. v+3 are in flight or ready while the consumers work on stage v.
         const u32x4_t *xp4 = (const u32x4_t *)a_xp;
         const int last_u4 = a_k_steps * MG * 64 - 1;
         const int pid = wave - NC;
