@@ -129,7 +129,10 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
     const int32_t *__restrict__ a_positions, const int32_t *__restrict__ a_row_ids, float a_inv_t, uint32_t a_key0,
     uint32_t a_key1, float *__restrict__ a_samp_z, float *__restrict__ a_samp_m, float *__restrict__ a_samp_s) {
     using GG = GemmGeom<MG, WK>;
-    constexpr int RING = HX_GEMM_RING, NBUF = GG::NBUF, LOOK = NBUF - 1;
+    // 8 m-groups: a step takes twice as long (matrix-core time), so half the ring covers the same latency and the
+    // revolution that fills it is half as long
+    constexpr int RING = MG >= 8 ? HX_GEMM_RING / 2 : HX_GEMM_RING;
+    constexpr int NBUF = GG::NBUF, LOOK = NBUF - 1;
     constexpr int KC = GG::KC, CPR = RING / KC, SLICE_U4 = GG::SLICE_U4, NC = WN * WK;
     // with at most 8 wavefronts per workgroup each may use 256 registers: enough to read B operands ahead
     constexpr bool PREFETCH_B = (NC + GG::NP <= 8) && MG <= 4;
