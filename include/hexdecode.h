@@ -187,6 +187,15 @@ int decode_step_sample(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_
 int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
 
+/* Checks the DEVICE-side inputs of a step before it is launched; decode_step itself trusts them (a wrong block id
+   or length makes its kernels read or write outside the pool).  Verified per row: 0 <= token < vocab;
+   0 <= position < max_seq_len and position < 16 * max_blocks_per_seq; seq_len == position + 1; every block id
+   of the first ceil(seq_len / 16) table entries in [0, num_blocks of kv).  Only the argument arrays are read.
+   SYNCHRONISES `stream`.  Returns HX_OK, or HX_E_RANGE with the first offending row in hx_last_error(). */
+int hx_validate_step_inputs(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *tokens,
+                            const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
+                            int32_t max_blocks_per_seq, void *stream);
+
 /* Parity hook: when attn_dev is not NULL every following decode_step also writes the attention
    output of every layer BEFORE its bf16 rounding to attn_dev, DEVICE fp32
    [n_layers, batch, n_q_heads * head_dim] (batch = that step's batch).  NULL switches it off. */

@@ -21,7 +21,7 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "decode_step_sample", "prefill_chunk", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
+           "decode_step", "decode_step_sample", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
            "hx_profile_enable", "hx_profile_read"]
 
@@ -72,6 +72,7 @@ def load():
         "hx_kv_gather": [vp, C.c_int, vp, vp, vp, vp, i32, i32, i64, vp],
         "decode_step": [vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp],
         "prefill_chunk": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
+        "hx_validate_step_inputs": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
         "decode_step_sample": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "hx_set_attn_capture": [vp, vp],
         "hx_stage_schedule": [vp, i32, vp, vp, vp, vp],
@@ -181,6 +182,11 @@ class Engine:
         B = tokens.numel()
         _check(load().decode_step(self.handle, kv.handle, B, _ptr(tokens), _ptr(positions), _ptr(seq_lens),
                                   _ptr(block_table), block_table.shape[1], _ptr(logits), _ptr(next_tokens), _stream()))
+
+    def validate_step_inputs(self, kv: "KVCache", tokens, positions, seq_lens, block_table) -> None:
+        """Raises HexError naming the first row whose device-side inputs are out of range (synchronises)."""
+        _check(load().hx_validate_step_inputs(self.handle, kv.handle, tokens.numel(), _ptr(tokens), _ptr(positions),
+                                              _ptr(seq_lens), _ptr(block_table), block_table.shape[1], _stream()))
 
     def prefill_chunk(self, kv: "KVCache", tokens, positions, seq_lens, block_table) -> None:
         """Rows = prompt tokens (<= max_batch); block_table holds one table row per ROW."""

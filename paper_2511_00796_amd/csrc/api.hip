@@ -452,6 +452,63 @@ extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const 
                     logprobs_out, &sp, true, stream);
 }
 
+// ---- validation of device-side inputs ---------------------------------------------------------------------------
+// One thread per row; the first offending row (smallest index) is reported as {code, row, value}.
+enum { HX_BAD_NONE = 0, HX_BAD_TOKEN = 1, HX_BAD_POSITION = 2, HX_BAD_SEQ_LEN = 3, HX_BAD_BLOCK = 4 };
+
+__global__ void validate_step_kernel(int batch, const int32_t *__restrict__ tokens, const int32_t *__restrict__ positions,
+                                     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ table,
+                                     int max_blocks, int vocab, int max_seq_len, long long num_blocks,
+                                     int32_t *__restrict__ report) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    int code = HX_BAD_NONE, value = 0;
+    const int tok = tokens[b], pos = positions[b], T = seq_lens[b];
+    if (tok < 0 || tok >= vocab) { code = HX_BAD_TOKEN; value = tok; }
+    else if (pos < 0 || pos >= max_seq_len || (long long)pos >= (long long)max_blocks * 16) { code = HX_BAD_POSITION; value = pos; }
+    else if (T != pos + 1) { code = HX_BAD_SEQ_LEN; value = T; }
+    else {
+        const int nblk = (T + 15) >> 4;                       // <= max_blocks by the position check
+        for (int i = 0; i < nblk; ++i) {
+            const int blk = table[(size_t)b * max_blocks + i];
+            if (blk < 0 || (long long)blk >= num_blocks) { code = HX_BAD_BLOCK; value = blk; break; }
+        }
+    }
+    (void)value;
+    if (code != HX_BAD_NONE) atomicMin(&report[0], b * 8 + code);   // smallest offending row wins, with its reason
+}
+
+extern "C" int hx_validate_step_inputs(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                                       const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, void *stream) {
+    int rc = check_step_args(e, kv, batch, max_blocks);
+    if (rc) return rc;
+    if (!kv) return hx_fail(HX_E_NULL, "kv is NULL");
+    if (!tokens || !positions || !seq_lens || !block_table) return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *report = (int32_t *)(e->ws + e->map.sched) + 8;             // 3 words of the per-step table area
+    const int32_t init = 0x7fffffff;
+    HX_CHECK_HIP(hipMemcpyAsync(report, &init, sizeof(init), hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(validate_step_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, batch, tokens, positions, seq_lens,
+                       block_table, max_blocks, e->cfg.vocab, e->cfg.max_seq_len, (long long)kv->num_blocks, report);
+    HX_CHECK_LAUNCH("validate_step");
+    int32_t out = 0;
+    HX_CHECK_HIP(hipMemcpyAsync(&out, report, sizeof(out), hipMemcpyDeviceToHost, st));
+    HX_CHECK_HIP(hipStreamSynchronize(st));
+    if (out == 0x7fffffff) return HX_OK;
+    const int row = out >> 3, code = out & 7;
+    int32_t value = 0;
+    const int32_t *src = code == HX_BAD_TOKEN ? tokens : code == HX_BAD_POSITION ? positions : seq_lens;
+    HX_CHECK_HIP(hipMemcpy(&value, src + row, sizeof(value), hipMemcpyDeviceToHost));
+    switch (code) {
+        case HX_BAD_TOKEN: return hx_fail(HX_E_RANGE, "row %d: token id %d is outside [0, %d)", row, value, e->cfg.vocab);
+        case HX_BAD_POSITION: return hx_fail(HX_E_RANGE, "row %d: position %d is outside the engine's max_seq_len %d or the %d table entries",
+                                             row, value, e->cfg.max_seq_len, max_blocks);
+        case HX_BAD_SEQ_LEN: return hx_fail(HX_E_RANGE, "row %d: seq_len %d is not position + 1", row, value);
+        default: return hx_fail(HX_E_RANGE, "row %d: a block id among its first %d table entries is outside [0, %lld)", row,
+                                (value + 15) / 16, (long long)kv->num_blocks);
+    }
+}
+
 // ---- single stages ---------------------------------------------------------------------------------------------------
 extern "C" int hx_stage_schedule(hx_engine *e, int32_t batch, const int32_t *seq_lens, int32_t *prefix_out,
                                  int32_t *sched_out, void *stream) {

@@ -175,3 +175,42 @@ def test_new_policy_version_packed_into_a_live_engine(hx):
     pack(live, 21)
     back = step(live, cache_for(live), tokens, ctx, table)
     assert torch.equal(back[0], out_a[0])
+
+
+def test_device_side_inputs_are_validated_without_running_the_step(hx):
+    """decode_step trusts its device arrays; hx_validate_step_inputs turns a bad token, position, length or block id
+    into an error that names the first offending row.  Only the validator runs on the bad inputs."""
+    eng = engine_with(hx, 9, max_batch=8, max_seq_len=200)
+    ctx = np.array([10, 150, 33, 64], dtype=np.int32)
+    table, n = synth.block_table(ctx + 1, 16, 4)
+    kv = hx.KVCache(eng, n)
+    tokens = np.array([1, 2, 3, 4], dtype=np.int32)
+
+    def check(tok=tokens, pos=ctx, lens=ctx + 1, tab=table):
+        eng.validate_step_inputs(kv, dev(np.asarray(tok, np.int32)), dev(np.asarray(pos, np.int32)),
+                                 dev(np.asarray(lens, np.int32)), dev(np.asarray(tab, np.int32)))
+
+    check()                                                   # the good inputs pass
+    bad = tokens.copy(); bad[2] = SHAPE.vocab
+    with pytest.raises(hx.HexError, match="row 2: token id"):
+        check(tok=bad)
+    bad = tokens.copy(); bad[1] = -1; bad[3] = -5
+    with pytest.raises(hx.HexError, match="row 1: token id -1"):
+        check(tok=bad)
+    pos = ctx.copy(); pos[0] = 200                            # == max_seq_len
+    with pytest.raises(hx.HexError, match="row 0: position 200"):
+        check(pos=pos, lens=pos + 1)
+    pos = ctx.copy(); pos[1] = table.shape[1] * 16            # beyond the table's columns
+    with pytest.raises(hx.HexError, match="row 1: position"):
+        check(pos=pos, lens=pos + 1)
+    lens = ctx + 1; lens[3] += 1
+    with pytest.raises(hx.HexError, match="row 3: seq_len 66 is not position"):
+        check(lens=lens)
+    tab = table.copy(); tab[1, 4] = n                         # one past the pool
+    with pytest.raises(hx.HexError, match="row 1: a block id"):
+        check(tab=tab)
+    tab = table.copy(); tab[2, 0] = -1
+    with pytest.raises(hx.HexError, match="row 2: a block id"):
+        check(tab=tab)
+    tab = table.copy(); tab[0, 3] = -7                        # past ceil(seq_len / 16) entries of row 0: ignored
+    check(tab=tab)
