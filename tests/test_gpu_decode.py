@@ -183,6 +183,53 @@ def test_chunked_prompt_processing_matches_dense_causal_recomputation(hx):
     print("chunked prompt processing: worst logit err / max|logit| %.3e" % worst)
 
 
+def test_chunked_prompt_processing_with_256_row_chunks(hx):
+    """A wider model (hidden 512, 14 query / 2 KV heads of 128, intermediate 1376, 2 layers) and five prompts of 3..300
+    tokens, processed 256 rows per call (the 8-group product path, several positions of every sequence in one call,
+    a ragged last chunk), then the last prompt token through decode_step: logits against the oracle's dense causal
+    recomputation of each prompt."""
+    s = synth.ModelShape("prefill-mid", 2, 512, 14, 2, 128, 1376, 2048)
+    seed = 77
+    ow, g, layers = host_model(s, seed)
+    cfg = oracle.make_config(s)
+    rng = np.random.default_rng(seed)
+    ctx = np.array([300, 3, 64, 129, 255], dtype=np.int32)
+    prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
+    table, nb = synth.block_table(ctx + 1, s.block_size, seed)
+    eng = hx.Engine(s, 256, int(ctx.max()) + 1)
+    for l in range(s.n_layers):
+        eng.pack_layer(l, synth.layer_weights(s, l, seed))
+    eng.pack_globals(synth.global_weights(s, seed))
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    # sequence-major order: a chunk holds long runs of consecutive positions of one sequence
+    rows = [(b, p) for b in range(len(ctx)) for p in range(int(ctx[b]) - 1)]
+    for at in range(0, len(rows), 256):
+        chunk = rows[at:at + 256]
+        bs = np.array([b for b, _ in chunk])
+        ps = np.array([p for _, p in chunk], dtype=np.int32)
+        toks = np.array([prompts[b][p] for b, p in chunk], dtype=np.int32)
+        eng.prefill_chunk(kv, dev(toks), dev(ps), dev(ps + 1), dev(table[bs]))
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[b][-1] for b in range(len(ctx))], dtype=np.int32)
+    logits = torch.empty(len(ctx), s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(len(ctx), dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    assert np.isfinite(gl).all()
+    worst = 0.0
+    for b in range(len(ctx)):
+        ref = oracle.full_causal(cfg, ow, prompts[b])[0][-1]
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(gl[b] - ref).max())
+        assert err <= LOGIT_TOL * scale, (b, err, scale)
+        worst = max(worst, err / scale)
+        top2 = np.sort(ref)[-2:]
+        assert int(nxt[b]) == int(np.argmax(ref)) or top2[1] - top2[0] < 4 * err
+    print("256-row prompt chunks: worst logit err / max|logit| %.3e" % worst)
+
+
 def test_decode_step_is_deterministic_and_tokens_are_argmax_of_logits(hx):
     from paper_2511_00796_amd import workload
     wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=48, lo=100, hi=3000)
