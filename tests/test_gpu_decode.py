@@ -340,6 +340,19 @@ def test_mid_size_full_batch_parity(hx):
     assert res[2] >= 0.995
 
 
+@pytest.mark.parametrize("batch,lo,hi", [(1, 16384, 16384), (2, 1, 1), (3, 15, 17)])
+def test_degenerate_batches_parity(hx, batch, lo, hi):
+    """Extremes of the attention schedule on 1.5B-shaped layers (2 of them): ONE sequence at the maximum length (its
+    2 x 1025 tiles spread over the 2048 wavefronts, a few tiles each, most wavefronts idle), sequences with a single
+    cached token (two keys), and lengths around one block.  With two keys nothing averages out: the second layer's
+    attention output moves by 6-8e-3 between the oracle and its own reordered evaluation (|o| ~ 2.5), so the floor of
+    the reordered oracle is taken into account as in the full-depth tests; the first layer agrees to 4e-6."""
+    wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=batch, lo=lo, hi=hi)
+    res, _ = run_sampled(hx, wl, 2, list(range(batch)), with_floor=True)
+    print("degenerate batch %d [%d,%d]: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f" % ((batch, lo, hi) + res))
+    assert res[2] == 1.0
+
+
 @pytest.mark.parametrize("name", ["1.5b-b64", "1.5b-b256-longtail", "7b-b128", "14b-b64"])
 def test_full_size_sampled_rows_parity(hx, name):
     """Configs 2-5 at full size, in the launch configuration the benchmark times: the oracle recomputes
