@@ -403,6 +403,73 @@ void orc_sample(const float *logits, int V, float temperature, uint64_t seed, ui
     *gap = best - second;
 }
 
+/* Nucleus (top-p) sampling, Holtzman et al., "The Curious Case of Neural Text Degeneration" (ICLR 2020), on the
+   temperature-scaled distribution p = softmax(z), z = logits / T as in orc_sample: order the vocabulary by
+   decreasing z, keep the shortest prefix whose probability mass reaches top_p, renormalise over it, draw from it.
+   Entries equal to the last kept z are all kept (their mutual order is arbitrary, so the kept set stays a
+   threshold set {z_i >= tau}).  The draw is the Gumbel-max of orc_sample restricted to the kept set, with the same
+   noise per vocabulary entry; logprob is that of the renormalised distribution, log(p_token / mass of the set).
+   Probabilities and the running mass are double.  margin = distance of top_p from the nearer of the two running
+   masses that decide the prefix length (the last one below top_p and the first one reaching it): a comparison in
+   another precision can decide differently only where margin is of the order of that precision. */
+typedef struct { float z; int32_t i; } orc_zi;
+static int orc_zi_desc(const void *a, const void *b) {
+    const orc_zi *x = (const orc_zi *)a, *y = (const orc_zi *)b;
+    if (x->z > y->z) return -1;
+    if (x->z < y->z) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+void orc_sample_top_p(const float *logits, int V, float temperature, float top_p, uint64_t seed, uint32_t row,
+                      uint32_t pos, int32_t *token, float *logprob, int32_t *nucleus_size, double *margin) {
+    const float inv_t = 1.0f / temperature;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    orc_zi *ord = (orc_zi *)malloc((size_t)V * sizeof(orc_zi));
+    unsigned char *kept = (unsigned char *)calloc((size_t)V, 1);
+    float zmax = -INFINITY;
+    for (int i = 0; i < V; ++i) {
+        ord[i].z = logits[i] * inv_t;
+        ord[i].i = i;
+        if (ord[i].z > zmax) zmax = ord[i].z;
+    }
+    double sum = 0.0;
+    for (int i = 0; i < V; ++i) sum += exp((double)ord[i].z - (double)zmax);
+    qsort(ord, (size_t)V, sizeof(orc_zi), orc_zi_desc);
+
+    double cum = 0.0, below = 0.0;
+    int n = 0;
+    while (n < V) {
+        below = cum;
+        cum += exp((double)ord[n].z - (double)zmax) / sum;
+        ++n;
+        if (cum >= (double)top_p) break;
+    }
+    *margin = fmin(fabs(cum - (double)top_p), fabs((double)top_p - below));
+    while (n < V && ord[n].z == ord[n - 1].z) ++n;
+    double mass = 0.0;
+    for (int k = 0; k < n; ++k) {
+        kept[ord[k].i] = 1;
+        mass += exp((double)ord[k].z - (double)zmax);
+    }
+
+    float best = -INFINITY;
+    int32_t best_i = ord[0].i;
+    for (int i = 0; i < V; ++i) {
+        if (!kept[i]) continue;
+        const uint32_t ctr[4] = {(uint32_t)(i / 4), row, pos, 0x53414D50u};
+        uint32_t r[4];
+        orc_philox4x32_10(ctr, key, r);
+        const float z = logits[i] * inv_t;
+        const float y = z - logf(-logf(orc_uniform_open(r[i % 4])));
+        if (y > best) { best = y; best_i = i; }
+    }
+    *token = best_i;
+    *logprob = (float)((double)(logits[best_i] * inv_t) - ((double)zmax + log(mass)));
+    *nucleus_size = n;
+    free(ord);
+    free(kept);
+}
+
 int orc_num_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);
