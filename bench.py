@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--sample", type=float, default=0.0, metavar="T",
                     help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
+    ap.add_argument("--top-p", type=float, default=1.0, metavar="P",
+                    help="with --sample: nucleus truncation (decode_step_top_p) at this mass")
     ap.add_argument("--prefill", type=int, default=0, metavar="P",
                     help="instead of decode steps, time prompt processing: 128 prompts of P tokens through prefill_chunk, "
                          "256 token rows per call (reported as prompt tokens/s)")
@@ -226,8 +228,12 @@ def main():
         s_lp = torch.zeros(wl.batch, dtype=torch.float32, device="cuda")
 
         def one_step():
-            eng.decode_step_sample(dw.kv, dw.tokens, dw.positions, dw.seq_lens_d, dw.table_d, args.sample, wl.seed,
-                                   dw.logits, s_tok, s_lp)
+            if args.top_p < 1.0:
+                eng.decode_step_top_p(dw.kv, dw.tokens, dw.positions, dw.seq_lens_d, dw.table_d, args.sample, args.top_p,
+                                      wl.seed, dw.logits, s_tok, s_lp)
+            else:
+                eng.decode_step_sample(dw.kv, dw.tokens, dw.positions, dw.seq_lens_d, dw.table_d, args.sample, wl.seed,
+                                       dw.logits, s_tok, s_lp)
     else:
         one_step = dw.step
 
@@ -256,7 +262,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
                    "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves(),
-                   "token_choice": ("sample T=%g + logprob" % args.sample) if args.sample > 0 else "greedy"},
+                   "token_choice": ("sample T=%g%s + logprob" % (args.sample, " top-p %g" % args.top_p if args.top_p < 1 else ""))
+                   if args.sample > 0 else "greedy"},
         "step_hbm": {"algorithmic_bytes": nbytes["total"], "weights_bytes": nbytes["weights"], "kv_bytes": nbytes["kv"],
                      "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
                      "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},

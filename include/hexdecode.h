@@ -176,6 +176,26 @@ int decode_step_sample(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_
                        int32_t max_blocks_per_seq, float temperature, uint64_t seed, const int32_t *row_ids,
                        float *logits_out, int32_t *tokens_out, float *logprobs_out, void *stream);
 
+/* The sampled step with nucleus (top-p) truncation (Holtzman et al., ICLR 2020) -- the paper does not say how
+   rollouts are drawn; this is the usual companion of the temperature.  With p = softmax(z), z as in
+   decode_step_sample, the kept set is {i : z_i >= tau}, tau the largest value for which the kept mass is at least
+   top_p (entries equal to the last kept one are all kept); the token is the Gumbel-max of decode_step_sample
+   restricted to the kept set, with the same noise per entry, so it is distributed as p renormalised over the set.
+   Arguments as decode_step_sample, plus:
+     top_p        in (0, 1].  1 is exactly decode_step_sample (no truncation).
+     logits_out   fp32 [batch, vocab]; REQUIRED when top_p < 1 (the selection re-reads the stored logits).
+     logprobs_out fp32 [batch]   log of the renormalised probability: z_token - log(sum over the kept set of exp(z_i)).
+     nucleus_sizes_out int32 [batch] or NULL: number of kept entries per row (top_p < 1 only).
+   Mass is accumulated in 40-bit fixed point, w_i = floor(exp(z_i - max z) * 2^40), with integer additions: the
+   kept set is exact in that arithmetic and the step stays deterministic.  A row whose running mass comes within
+   ~1e-7 of top_p at the cut may keep one entry more or less than a double-precision evaluation would.
+   Errors: HX_E_RANGE for temperature or top_p out of range, HX_E_NULL for missing outputs. */
+int decode_step_top_p(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *tokens,
+                      const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
+                      int32_t max_blocks_per_seq, float temperature, float top_p, uint64_t seed,
+                      const int32_t *row_ids, float *logits_out, int32_t *tokens_out, float *logprobs_out,
+                      int32_t *nucleus_sizes_out, void *stream);
+
 /* Prompt processing in chunks: the step for n_rows (<= max_batch) PROMPT TOKENS at once, without LM head -- only the
    K and V of every row enter the cache (rollouts start from a prompt: paper Section 1, stage (i); Section 4.2.2).
    A row is one token of one sequence: tokens[r] at positions[r], attending seq_lens[r] = positions[r] + 1 keys
@@ -250,6 +270,14 @@ int hx_stage_rmsnorm(hx_engine *engine, int gain_kind, int layer, int32_t batch,
    [batch], may be NULL) receives the greedy token; it must be NULL for the other kinds. */
 int hx_stage_linear(hx_engine *engine, int matrix_kind, int layer, int32_t batch, const float *x_dev,
                     float *y_dev, int32_t *argmax_out_dev, void *stream);
+
+/* The LM head on caller-supplied activations followed by the nucleus draw of decode_step_top_p (same kernels, same
+   argument meaning; top_p in (0, 1), all outputs but nucleus_sizes_out required): x_dev fp32 [batch, hidden] is
+   rounded to bf16 on entry, logits_out fp32 [batch, vocab] receives R(x) W. */
+int hx_stage_lm_head_top_p(hx_engine *engine, int32_t batch, const float *x_dev, const int32_t *positions,
+                           const int32_t *row_ids, float temperature, float top_p, uint64_t seed,
+                           float *logits_out, int32_t *tokens_out, float *logprobs_out,
+                           int32_t *nucleus_sizes_out, void *stream);
 
 /* ---- per-kernel timing (measurement hook) -------------------------------------------------------------- */
 

@@ -97,7 +97,7 @@ def _load(path):
     L.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
     L.orc_sample_top_p.restype = None
     L.orc_sample_top_p.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
-                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.orc_philox4x32_10.restype = None
     return L
 
@@ -229,7 +229,8 @@ def sample(logits, temperature: float, seed: int, rows, positions):
 def sample_top_p(logits, temperature: float, top_p: float, seed: int, rows, positions):
     """Nucleus (top-p) sample of every row of ``logits`` [B, V] after temperature scaling.
     Returns (tokens int32 [B], logprobs float32 [B] under the renormalised kept set, sizes int32 [B] of the kept
-    set, margins float64 [B]: distance of top_p from the running masses that decide the size)."""
+    set, margins float64 [B]: distance of top_p from the running masses that decide the size, gaps float32 [B]:
+    best minus runner-up perturbed score among the kept entries)."""
     x = _f32(logits)
     if x.ndim == 1:
         x = x[None]
@@ -240,12 +241,13 @@ def sample_top_p(logits, temperature: float, top_p: float, seed: int, rows, posi
     lp = np.zeros(B, dtype=np.float32)
     size = np.zeros(B, dtype=np.int32)
     margin = np.zeros(B, dtype=np.float64)
+    gap = np.zeros(B, dtype=np.float32)
     for b in range(B):
         xb = np.ascontiguousarray(x[b])
         lib().orc_sample_top_p(_p(xb), V, C.c_float(temperature), C.c_float(top_p), C.c_uint64(seed),
                                C.c_uint32(int(rows[b])), C.c_uint32(int(positions[b])), tok[b:].ctypes.data,
-                               lp[b:].ctypes.data, size[b:].ctypes.data, margin[b:].ctypes.data)
-    return tok, lp, size, margin
+                               lp[b:].ctypes.data, size[b:].ctypes.data, margin[b:].ctypes.data, gap[b:].ctypes.data)
+    return tok, lp, size, margin, gap
 
 
 # ---- model-level objects -----------------------------------------------------------------------

@@ -411,7 +411,8 @@ void orc_sample(const float *logits, int V, float temperature, uint64_t seed, ui
    noise per vocabulary entry; logprob is that of the renormalised distribution, log(p_token / mass of the set).
    Probabilities and the running mass are double.  margin = distance of top_p from the nearer of the two running
    masses that decide the prefix length (the last one below top_p and the first one reaching it): a comparison in
-   another precision can decide differently only where margin is of the order of that precision. */
+   another precision can decide differently only where margin is of the order of that precision.  gap = best minus
+   runner-up of the perturbed scores among the kept entries. */
 typedef struct { float z; int32_t i; } orc_zi;
 static int orc_zi_desc(const void *a, const void *b) {
     const orc_zi *x = (const orc_zi *)a, *y = (const orc_zi *)b;
@@ -421,7 +422,7 @@ static int orc_zi_desc(const void *a, const void *b) {
 }
 
 void orc_sample_top_p(const float *logits, int V, float temperature, float top_p, uint64_t seed, uint32_t row,
-                      uint32_t pos, int32_t *token, float *logprob, int32_t *nucleus_size, double *margin) {
+                      uint32_t pos, int32_t *token, float *logprob, int32_t *nucleus_size, double *margin, float *gap) {
     const float inv_t = 1.0f / temperature;
     const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     orc_zi *ord = (orc_zi *)malloc((size_t)V * sizeof(orc_zi));
@@ -452,7 +453,7 @@ void orc_sample_top_p(const float *logits, int V, float temperature, float top_p
         mass += exp((double)ord[k].z - (double)zmax);
     }
 
-    float best = -INFINITY;
+    float best = -INFINITY, second = -INFINITY;
     int32_t best_i = ord[0].i;
     for (int i = 0; i < V; ++i) {
         if (!kept[i]) continue;
@@ -461,11 +462,13 @@ void orc_sample_top_p(const float *logits, int V, float temperature, float top_p
         orc_philox4x32_10(ctr, key, r);
         const float z = logits[i] * inv_t;
         const float y = z - logf(-logf(orc_uniform_open(r[i % 4])));
-        if (y > best) { best = y; best_i = i; }
+        if (y > best) { second = best; best = y; best_i = i; }
+        else if (y > second) second = y;
     }
     *token = best_i;
     *logprob = (float)((double)(logits[best_i] * inv_t) - ((double)zmax + log(mass)));
     *nucleus_size = n;
+    *gap = best - second;                         /* +inf when one entry is kept */
     free(ord);
     free(kept);
 }

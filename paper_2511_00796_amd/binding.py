@@ -21,8 +21,8 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "decode_step_sample", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
-           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear",
+           "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
+           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
            "hx_profile_enable", "hx_profile_read"]
 
 KERNEL_CLASSES = ["attention", "combine", "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm", "norm",
@@ -74,6 +74,7 @@ def load():
         "prefill_chunk": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
         "hx_validate_step_inputs": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
         "decode_step_sample": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
+        "decode_step_top_p": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp, vp],
         "hx_set_attn_capture": [vp, vp],
         "hx_stage_schedule": [vp, i32, vp, vp, vp, vp],
         "hx_attention_waves": [vp],
@@ -82,6 +83,7 @@ def load():
         "hx_stage_attention": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],
         "hx_stage_linear": [vp, C.c_int, C.c_int, i32, vp, vp, vp, vp],
+        "hx_stage_lm_head_top_p": [vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "hx_profile_enable": [vp, C.c_uint32],
         "hx_profile_read": [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     }
@@ -202,6 +204,15 @@ class Engine:
                                          C.c_uint64(seed), _ptr(row_ids), _ptr(logits), _ptr(out_tokens),
                                          _ptr(out_logprobs), _stream()))
 
+    def decode_step_top_p(self, kv: "KVCache", tokens, positions, seq_lens, block_table, temperature: float, top_p: float,
+                          seed: int, logits: Optional[torch.Tensor], out_tokens: torch.Tensor, out_logprobs: torch.Tensor,
+                          row_ids: Optional[torch.Tensor] = None, out_sizes: Optional[torch.Tensor] = None) -> None:
+        B = tokens.numel()
+        _check(load().decode_step_top_p(self.handle, kv.handle, B, _ptr(tokens), _ptr(positions), _ptr(seq_lens),
+                                        _ptr(block_table), block_table.shape[1], C.c_float(temperature), C.c_float(top_p),
+                                        C.c_uint64(seed), _ptr(row_ids), _ptr(logits), _ptr(out_tokens),
+                                        _ptr(out_logprobs), _ptr(out_sizes), _stream()))
+
     def set_attn_capture(self, buf: Optional[torch.Tensor]) -> None:
         self._capture = buf
         _check(load().hx_set_attn_capture(self.handle, _ptr(buf)))
@@ -258,6 +269,19 @@ class Engine:
         am = torch.empty(B, dtype=torch.int32, device=self.device) if want_argmax else None
         _check(load().hx_stage_linear(self.handle, kind, layer, B, _ptr(x), _ptr(y), _ptr(am), _stream()))
         return (y, am) if want_argmax else y
+
+    def stage_lm_head_top_p(self, x: torch.Tensor, positions: torch.Tensor, temperature: float, top_p: float, seed: int,
+                            row_ids: Optional[torch.Tensor] = None):
+        """-> (logits fp32 [B, vocab], tokens int32 [B], logprobs fp32 [B], kept-set sizes int32 [B])"""
+        B = x.shape[0]
+        y = torch.empty(B, self.shape.vocab, dtype=torch.float32, device=self.device)
+        tok = torch.empty(B, dtype=torch.int32, device=self.device)
+        lp = torch.empty(B, dtype=torch.float32, device=self.device)
+        n = torch.empty(B, dtype=torch.int32, device=self.device)
+        _check(load().hx_stage_lm_head_top_p(self.handle, B, _ptr(x), _ptr(positions), _ptr(row_ids), C.c_float(temperature),
+                                             C.c_float(top_p), C.c_uint64(seed), _ptr(y), _ptr(tok), _ptr(lp), _ptr(n),
+                                             _stream()))
+        return y, tok, lp, n
 
 
 class KVCache:

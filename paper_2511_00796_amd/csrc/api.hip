@@ -412,7 +412,12 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wd, batch), (size_t)batch * c->hidden, next_gain, st));
     }
     if (!with_head) return HX_OK;
-    if (sample) {
+    if (sample && sample->top_p < 1.0f) {
+        // the kept set needs every logit of the row again: the head writes them (with its per-tile maxima), then
+        // one workgroup per row selects and draws
+        HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st));
+        HX_TIMED(HX_K_SETUP, hx_launch_nucleus(e, batch, logits_out, sample, next_tokens_out, logprobs_out, st));
+    } else if (sample) {
         HX_TIMED(HX_K_GEMM_LM, hx_launch_gemm(e, &e->wlm, batch, ws + e->map.xp, HX_EPI_SAMPLE, logits_out, nullptr, st, sample));
         HX_TIMED(HX_K_SETUP, hx_launch_sample_final(e, batch, next_tokens_out, logprobs_out, st));
     } else {
@@ -448,6 +453,30 @@ extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const 
     sp.inv_temperature = 1.0f / temperature;
     sp.key0 = (uint32_t)seed;
     sp.key1 = (uint32_t)(seed >> 32);
+    sp.top_p = 1.0f;
+    sp.nucleus_sizes = nullptr;
+    return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, tokens_out,
+                    logprobs_out, &sp, true, stream);
+}
+
+extern "C" int decode_step_top_p(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
+                                 const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks,
+                                 float temperature, float top_p, uint64_t seed, const int32_t *row_ids, float *logits_out,
+                                 int32_t *tokens_out, float *logprobs_out, int32_t *nucleus_sizes_out, void *stream) {
+    if (!(temperature > 0.0f) || !(temperature < 1e30f))
+        return hx_fail(HX_E_RANGE, "temperature %g must be positive and finite", (double)temperature);
+    if (!(top_p > 0.0f) || !(top_p <= 1.0f)) return hx_fail(HX_E_RANGE, "top_p %g must be in (0, 1]", (double)top_p);
+    if (!logprobs_out) return hx_fail(HX_E_NULL, "logprobs_out is NULL");
+    if (top_p < 1.0f && !logits_out) return hx_fail(HX_E_NULL, "logits_out is NULL (the kept set is selected from the stored logits)");
+    if (top_p >= 1.0f && nucleus_sizes_out) return hx_fail(HX_E_RANGE, "nucleus_sizes_out is only written for top_p < 1");
+    hx_sample_params sp;
+    sp.positions = positions;
+    sp.row_ids = row_ids;
+    sp.inv_temperature = 1.0f / temperature;
+    sp.key0 = (uint32_t)seed;
+    sp.key1 = (uint32_t)(seed >> 32);
+    sp.top_p = top_p;
+    sp.nucleus_sizes = nucleus_sizes_out;
     return run_step(e, kv, batch, tokens, positions, seq_lens, block_table, max_blocks, logits_out, tokens_out,
                     logprobs_out, &sp, true, stream);
 }
@@ -563,6 +592,30 @@ extern "C" int hx_stage_rmsnorm(hx_engine *e, int gain_kind, int layer, int32_t 
         else return hx_fail(HX_E_SHAPE, "tensor kind %d is not a gain", gain_kind);
     }
     return hx_launch_norm_only(e, batch, x_dev, off, y_dev, (hipStream_t)stream);
+}
+
+extern "C" int hx_stage_lm_head_top_p(hx_engine *e, int32_t batch, const float *x_dev, const int32_t *positions,
+                                      const int32_t *row_ids, float temperature, float top_p, uint64_t seed,
+                                      float *logits_out, int32_t *tokens_out, float *logprobs_out,
+                                      int32_t *nucleus_sizes_out, void *stream) {
+    int rc = check_step_args(e, nullptr, batch, 1);
+    if (rc) return rc;
+    if (!x_dev || !positions || !logits_out || !tokens_out || !logprobs_out) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (!(temperature > 0.0f) || !(temperature < 1e30f))
+        return hx_fail(HX_E_RANGE, "temperature %g must be positive and finite", (double)temperature);
+    if (!(top_p > 0.0f) || !(top_p < 1.0f)) return hx_fail(HX_E_RANGE, "top_p %g must be in (0, 1)", (double)top_p);
+    hipStream_t st = (hipStream_t)stream;
+    hx_sample_params sp;
+    sp.positions = positions;
+    sp.row_ids = row_ids;
+    sp.inv_temperature = 1.0f / temperature;
+    sp.key0 = (uint32_t)seed;
+    sp.key1 = (uint32_t)(seed >> 32);
+    sp.top_p = top_p;
+    sp.nucleus_sizes = nucleus_sizes_out;
+    if ((rc = hx_launch_pack_x(e, batch, x_dev, e->cfg.hidden, e->ws + e->map.xp, st))) return rc;
+    if ((rc = hx_launch_gemm(e, &e->wlm, batch, e->ws + e->map.xp, HX_EPI_LOGITS, logits_out, nullptr, st))) return rc;
+    return hx_launch_nucleus(e, batch, logits_out, &sp, tokens_out, logprobs_out, st);
 }
 
 extern "C" int hx_stage_linear(hx_engine *e, int kind, int layer, int32_t batch, const float *x_dev, float *y_dev,

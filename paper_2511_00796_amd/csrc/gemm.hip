@@ -89,20 +89,6 @@ __device__ __forceinline__ u32x4_t hx_stream_load(const uint4 *p) {   // read-on
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
 #define HX_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
-// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), from its published definition: ten rounds of
-// (c0, c1, c2, c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0)), key += (W0, W1) per round.
-__device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                                 uint32_t k1, uint32_t (&out)[4]) {
-#pragma unroll
-    for (int round = 0; round < 10; ++round) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
-        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
 template <int MG, int WK> struct GemmGeom {
     // stages: 4 x 32 KiB; with 8 m-groups 2 x 64 KiB, so that a stage still holds 8 k-steps (one barrier per 8)
     static constexpr int NBUF = MG >= 8 ? 2 : 4;

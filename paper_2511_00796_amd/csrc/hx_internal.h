@@ -181,7 +181,27 @@ struct hx_sample_params {
     const int32_t *row_ids;     // device [batch] or NULL (row id = index in the batch)
     float inv_temperature;
     uint32_t key0, key1;        // seed, low and high word
+    float top_p;                // 1: no truncation; (0, 1): nucleus of that mass
+    int32_t *nucleus_sizes;     // device [batch] or NULL: size of each row's kept set (top_p < 1)
 };
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), from its published definition: ten rounds of
+// (c0, c1, c2, c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0)), key += (W0, W1) per round.
+__device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// sampling.hip
+int hx_launch_nucleus(const hx_engine *e, int batch, const float *logits, const hx_sample_params *sample,
+                      int32_t *tokens_out, float *logprobs_out, hipStream_t st);
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue,
                    float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st,
                    const hx_sample_params *sample = nullptr);

@@ -19,11 +19,11 @@ def test_kept_set_sizes_of_a_hand_worked_distribution():
     p = np.array([0.15, 0.5, 0.05, 0.3])
     logits = np.log(p).astype(np.float32) + 3.0          # softmax is shift invariant
     for top_p, size in ((0.4, 1), (0.75, 2), (0.85, 3), (0.96, 4)):
-        _, _, n, margin = oracle.sample_top_p(_rows(logits, 1), 1.0, top_p, 1, [0], [0])
+        _, _, n, margin, _ = oracle.sample_top_p(_rows(logits, 1), 1.0, top_p, 1, [0], [0])
         assert n[0] == size, (top_p, n)
         assert margin[0] > 0.009
     # the margin is the distance to the nearer deciding mass: top_p = 0.79 sits 0.01 below 0.8
-    _, _, n, margin = oracle.sample_top_p(_rows(logits, 1), 1.0, 0.79, 1, [0], [0])
+    _, _, n, margin, _ = oracle.sample_top_p(_rows(logits, 1), 1.0, 0.79, 1, [0], [0])
     assert n[0] == 2 and abs(margin[0] - 0.01) < 1e-6
 
 
@@ -38,7 +38,7 @@ def test_temperature_is_applied_before_the_cut():
 def test_small_top_p_is_greedy_with_certainty():
     rng = np.random.default_rng(5)
     x = rng.normal(0, 1.5, size=(50, 300)).astype(np.float32)
-    tok, lp, n, _ = oracle.sample_top_p(x, 0.8, 1e-6, 77, np.arange(50), np.arange(50))
+    tok, lp, n, _, _ = oracle.sample_top_p(x, 0.8, 1e-6, 77, np.arange(50), np.arange(50))
     assert np.array_equal(tok, x.argmax(axis=1))
     assert np.all(n == 1) and np.all(lp == 0.0)
 
@@ -48,7 +48,7 @@ def test_top_p_near_one_is_the_plain_sampler():
     rng = np.random.default_rng(6)
     x = rng.normal(0, 1.0, size=(40, 64)).astype(np.float32)
     rows, pos = np.arange(40) + 3, np.arange(40) * 7
-    tok, lp, n, _ = oracle.sample_top_p(x, 1.3, 0.99999994, 1234, rows, pos)
+    tok, lp, n, _, _ = oracle.sample_top_p(x, 1.3, 0.99999994, 1234, rows, pos)
     tok0, lp0, _ = oracle.sample(x, 1.3, 1234, rows, pos)
     assert np.all(n == 64)
     assert np.array_equal(tok, tok0)
@@ -57,7 +57,7 @@ def test_top_p_near_one_is_the_plain_sampler():
 
 def test_entries_tied_with_the_last_kept_one_are_kept():
     logits = np.array([0.0, -10.0, 0.0, 0.0], dtype=np.float32)
-    tok, lp, n, _ = oracle.sample_top_p(_rows(logits, 3000), 1.0, 0.2, 9, np.arange(3000), np.zeros(3000))
+    tok, lp, n, _, _ = oracle.sample_top_p(_rows(logits, 3000), 1.0, 0.2, 9, np.arange(3000), np.zeros(3000))
     assert np.all(n == 3)
     assert set(np.unique(tok)) == {0, 2, 3}
     assert np.allclose(lp, np.log(1.0 / 3.0), atol=1e-6)
@@ -76,7 +76,7 @@ def test_draws_follow_the_renormalised_kept_set():
     size = int(np.searchsorted(np.cumsum(p[order]), top_p) + 1)
     kept = order[:size]
     assert 1 < size < len(logits)
-    tok, lp, n, _ = oracle.sample_top_p(_rows(logits, N), temperature, top_p, 4242, np.arange(N), np.full(N, 11))
+    tok, lp, n, _, _ = oracle.sample_top_p(_rows(logits, N), temperature, top_p, 4242, np.arange(N), np.full(N, 11))
     assert np.all(n == size)
     assert set(np.unique(tok)) <= set(int(k) for k in kept)
     q = p[kept] / p[kept].sum()
@@ -97,7 +97,7 @@ def test_kept_set_and_logprob_against_a_library_sort_in_float64():
     V, B = 20000, 6
     x = rng.normal(0, 1.2, size=(B, V)).astype(np.float32)
     for temperature, top_p in ((1.0, 0.9), (0.7, 0.5), (1.5, 0.95)):
-        tok, lp, n, margin = oracle.sample_top_p(x, temperature, top_p, 31, np.arange(B), np.arange(B) + 100)
+        tok, lp, n, margin, _ = oracle.sample_top_p(x, temperature, top_p, 31, np.arange(B), np.arange(B) + 100)
         z = (x * np.float32(1.0 / np.float32(temperature))).astype(np.float32).astype(np.float64)
         for b in range(B):
             assert margin[b] > 1e-9
