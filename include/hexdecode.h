@@ -203,7 +203,9 @@ int decode_step_top_p(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t
    sequence in one call must cover consecutive positions that continue its cache (K and V of all rows are written
    before any row attends, so a row sees the rows before it); chunks of a sequence are submitted in position order.
    The last prompt token is then given to decode_step / decode_step_sample, which yields the first generated token.
-   Arguments, ownership and errors as decode_step. */
+   Consecutive rows that continue one another (seq_lens one more, the same table row) are attended in groups of up
+   to 8 that share one read of the cache, so a call should hold long runs of one sequence rather than one row of
+   many; any row order is correct.  Arguments, ownership and errors as decode_step. */
 int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
 
@@ -235,7 +237,9 @@ int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention 
    same tolerances, only summation order changes):
      HX_ATTN_WAVES=n        wavefronts of the attention kernel, read at hx_engine_create (default 2048 = 8 per CU)
      HX_GEMM_SHAPE=wn,wk,s  force tiles per workgroup (4..6, or 4 with wk = 2), k-slices per workgroup and K-splits
-     HX_GEMM_MAX_SPLITS=s   upper bound of the planner's K-splits (1..9)                                            */
+     HX_GEMM_MAX_SPLITS=s   upper bound of the planner's K-splits (1..9)
+     HX_CHUNK_ATTENTION=0   prefill_chunk attends every row on its own (the decode step's kernel) instead of in groups
+                            of consecutive rows, read at hx_engine_create; for comparison                            */
 
 /* How a matrix product of n_tiles 32-column tiles and k_steps 16-row steps is launched for `batch` rows (host logic
    only, no GPU work): tiles per workgroup, k-slices per workgroup, and K-splits whose fp32 partial results the consumer

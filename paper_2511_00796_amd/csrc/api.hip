@@ -123,6 +123,11 @@ static size_t map_workspace(hx_engine *e) {
     const size_t slots = (size_t)e->attn_waves + B * c->n_kv_heads;
     m->part_ml = take(slots * 32 * 4);
     m->part_o = take(slots * e->G * e->D * 4);
+    m->chunk_cont = take(256 * 4);
+    m->chunk_ginfo = take(256 * 4);
+    m->chunk_rgrp = take(256 * 4);
+    m->chunk_part_ml = take(slots * 4 * 32 * 4);
+    m->chunk_part_o = take(slots * 4 * 16 * e->D * 4);
     m->amax_val = take(B * e->wlm.n_tiles * 4);
     m->amax_idx = take(B * e->wlm.n_tiles * 4);
     m->samp_z = take(B * e->wlm.n_tiles * 4);
@@ -145,6 +150,9 @@ static int init_engine_shape(hx_engine *e, const hx_model_config *cfg) {
     e->G = d.G; e->D = d.D; e->q_dim = d.q_dim; e->kv_dim = d.kv_dim; e->qkv_dim = d.qkv_dim;
     e->m_groups_max = hx_m_groups(cfg->max_batch);
     e->attn_waves = attention_waves();
+    // HX_CHUNK_ATTENTION=0: prompt rows go through the decode step's attention, one K/V stream per row (comparison)
+    const char *ca = getenv("HX_CHUNK_ATTENTION");
+    e->chunk_attention = e->G <= HX_CHUNK_ROWS && !(ca && atoi(ca) == 0);
     return HX_OK;
 }
 
@@ -395,6 +403,9 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
     const size_t attn_stride = (size_t)batch * e->q_dim;
 
     HX_TIMED(HX_K_SETUP, hx_launch_step_setup(e, batch, positions, seq_lens, st));
+    // prompt rows: consecutive rows of a sequence share one K/V stream (their schedule replaces the decode step's)
+    const bool chunked = !with_head && e->chunk_attention;
+    if (chunked) HX_TIMED(HX_K_SETUP, hx_launch_chunk_setup(e, batch, seq_lens, block_table, max_blocks, st));
     HX_TIMED(HX_K_NORM, hx_launch_embed_norm(e, batch, tokens, e->layers[0].g1, st));
     for (int l = 0; l < c->n_layers; ++l) {
         const hx_layer_map *lm = &e->layers[l];
@@ -402,8 +413,14 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
         HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, hx_gemm_splits(&lm->wqkv, batch), (size_t)batch * e->qkv_dim,
                                                  positions, block_table, max_blocks, st));
         if (!with_head && l + 1 == c->n_layers) break;   // prompt rows: of the last layer only its K and V are needed
-        HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
-        HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, e->attn_capture ? e->attn_capture + l * attn_stride : nullptr, st));
+        float *capture = e->attn_capture ? e->attn_capture + l * attn_stride : nullptr;
+        if (chunked) {
+            HX_TIMED(HX_K_ATTENTION, hx_launch_chunk_attention(e, kv, l, block_table, max_blocks, st));
+            HX_TIMED(HX_K_COMBINE, hx_launch_chunk_combine(e, batch, capture, st));
+        } else {
+            HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
+            HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, capture, st));
+        }
         HX_TIMED(HX_K_GEMM_O, hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st));
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(e, batch, ypart, hx_gemm_splits(&lm->wo, batch), (size_t)batch * c->hidden, lm->g2, st));
         HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm(e, &lm->wgu, batch, ws + e->map.xp, HX_EPI_SWIGLU, nullptr, ws + e->map.mp, st));

@@ -40,6 +40,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define HX_BLOCK_TOKENS 16
 #define HX_MAX_HIDDEN 8192
 #define HX_PREFIX_LEN 320    // entries of the per-step block prefix (max_batch 256 + 1, padded to 5 x 64)
+#define HX_CHUNK_ROWS 8      // consecutive prompt rows of one sequence that share a K/V stream (8 x G <= 64 columns)
 #define HX_MAX_SPLITS 9       // K-splits of a product whose partials are summed by its consumer kernel
 
 // ---- error reporting (api.hip) -------------------------------------------------------------------
@@ -121,6 +122,12 @@ struct hx_ws_map {          // byte offsets in the workspace
     size_t pre, lens, sched;  // int32 attention schedule: block prefix [HX_PREFIX_LEN], lengths [256], {S, Nt}
     size_t part_ml;         // fp32 [slots][32]     running max (16) | sum (16); slots = attn_waves + max_batch*n_kv
     size_t part_o;          // fp32 [slots][G][D]   unnormalised partial outputs
+    // prompt chunks (attention_chunk.hip): rows grouped by sequence, partial results of 4 column blocks per slot
+    size_t chunk_cont;      // int32 [256]  row r continues row r - 1
+    size_t chunk_ginfo;     // int32 [256]  group: first row | rows << 16
+    size_t chunk_rgrp;      // int32 [256]  row: group | index in group << 16
+    size_t chunk_part_ml;   // fp32 [slots][4][32]
+    size_t chunk_part_o;    // fp32 [slots][4][16][D]
     size_t amax_val, amax_idx;  // fp32 / int32 [max_batch][lm n_tiles]   (sampling: best perturbed score and its column)
     size_t samp_z, samp_m, samp_s;  // fp32 [max_batch][lm n_tiles]: scaled logit of the candidate, tile max, tile sum of exp
     size_t scratch_f32;     // fp32 [max_batch][max(hidden, q_dim, inter, qkv_dim)] stage-hook staging
@@ -132,6 +139,7 @@ struct hx_engine {
     int G, D, q_dim, kv_dim, qkv_dim;
     int m_groups_max;       // ceil(max_batch / 32)
     int attn_waves;         // wavefronts of the attention kernel (8 per compute unit)
+    bool chunk_attention;     // prompt rows of one sequence share a K/V stream (G <= 8; HX_CHUNK_ATTENTION=0 disables)
     char *weights;          // device
     char *ws;               // device
     size_t weights_bytes, ws_bytes;
@@ -198,6 +206,13 @@ __device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint3
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
+
+// attention_chunk.hip
+int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_lens, const int32_t *table, int max_blocks,
+                          hipStream_t st);
+int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
+                              hipStream_t st);
+int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st);
 
 // sampling.hip
 int hx_launch_nucleus(const hx_engine *e, int batch, const float *logits, const hx_sample_params *sample,
