@@ -46,7 +46,7 @@ def build(force: bool = True, descending: bool = False) -> str:
 
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
-                                         "intermediate", "vocab", "block_size", "qkv_bias", "round_act")]
+                                         "intermediate", "vocab", "block_size", "qkv_bias", "round_act", "kv_fp8")]
     _fields_ += [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
@@ -91,6 +91,8 @@ def _load(path):
     L.orc_head.restype = C.c_int32
     L.orc_decode_step.restype = C.c_int
     L.orc_num_threads.restype = C.c_int
+    L.orc_e4m3_round.restype = C.c_float
+    L.orc_e4m3_round.argtypes = [C.c_float]
     L.orc_uniform_open.restype = C.c_float
     L.orc_uniform_open.argtypes = [C.c_uint32]
     L.orc_sample.restype = None
@@ -132,14 +134,26 @@ def _i32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def make_config(shape, round_act: bool = True, block_size: Optional[int] = None) -> _Config:
-    """orc_config from any object with the ModelShape field names."""
+def make_config(shape, round_act: bool = True, block_size: Optional[int] = None, kv_fp8: bool = False) -> _Config:
+    """orc_config from any object with the ModelShape field names.  kv_fp8: the 8-bit (E4M3) cache variant."""
     return _Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                    shape.intermediate, shape.vocab, block_size or shape.block_size,
-                   1 if shape.qkv_bias else 0, 1 if round_act else 0, shape.rms_eps, shape.rope_theta)
+                   1 if shape.qkv_bias else 0, 1 if round_act else 0, 1 if kv_fp8 else 0, shape.rms_eps,
+                   shape.rope_theta)
 
 
 # ---- elementary operations (used by the pins) ------------------------------------------------
+
+def e4m3_round(x) -> np.ndarray:
+    """Nearest E4M3 value (ties to even, saturating at 448) of every fp32 element."""
+    a = _f32(x)
+    out = np.empty(a.shape, dtype=np.float32)
+    f = lib().orc_e4m3_round
+    flat_in, flat_out = a.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = f(C.c_float(float(flat_in[i])))
+    return out
+
 
 def bf16_round_bits(x) -> np.ndarray:
     """uint16 bf16 patterns of fp32 values, through the oracle's own rounding."""

@@ -14,6 +14,8 @@
  * activation is rounded to bf16 (round-to-nearest-even) at exactly these points: the input of
  * each of the five matrix products, the rotated query, and K / V on entering the cache.  With
  * round_act = 0 those roundings are skipped (used only to compare with fp32 library code).
+ * With kv_fp8 = 1, K and V enter the cache rounded to the 8-bit format E4M3 instead (a later variant
+ * that halves the dominant byte term; everything else is unchanged).
  *
  * Nothing here is blocked, fused, tiled or reordered.  It shares no code, table or header
  * with the GPU library.  Only tests, the smoke check and the benchmark's CPU-baseline leg call
@@ -32,6 +34,7 @@ typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab, block_size;
     int32_t qkv_bias;  /* 1: add the q/k/v bias                                   */
     int32_t round_act; /* 1: bf16 rounding points on (the contract); 0: pure fp32 */
+    int32_t kv_fp8;    /* 1: K and V enter the cache as 8-bit floats (E4M3), see orc_e4m3_round */
     float rms_eps, rope_theta;
 } orc_config;
 
@@ -67,6 +70,34 @@ uint16_t orc_f32_to_bf16(float f) {
 
 static float round_act(const orc_config *c, float f) {
     return c->round_act ? orc_bf16_to_f32(orc_f32_to_bf16(f)) : f;
+}
+
+/* ---- 8-bit cache variant ------------------------------------------------------------------ */
+
+/* Nearest value of the 8-bit floating-point format E4M3 of the OCP 8-bit floating point specification (1 sign,
+   4 exponent bits with bias 7, 3 mantissa bits; no infinities; largest finite value 448 = 1.75 * 2^8; subnormals
+   are multiples of 2^-9 below 2^-6), ties to the even mantissa, magnitudes above 448 saturate to 448.  Every such
+   value is exactly a bf16 value, so the cache keeps holding bf16 patterns; the variant only changes the rounding
+   K and V undergo on entering the cache -- directly from fp32, not through bf16 first. */
+float orc_e4m3_round(float f) {
+    if (f != f) return f;
+    float a = fabsf(f);
+    if (a > 448.0f) a = 448.0f;
+    float q;
+    if (a < 0.015625f) {                       /* below 2^-6: subnormal, spacing 2^-9 */
+        q = nearbyintf(a * 512.0f) / 512.0f;   /* exact scalings; nearbyint rounds half to even */
+    } else {
+        int e;
+        frexpf(a, &e);                         /* a = m * 2^e, m in [0.5, 1): spacing 2^(e - 4) */
+        float ulp = ldexpf(1.0f, e - 4);
+        q = nearbyintf(a / ulp) * ulp;         /* may carry into the next binade: still a format value */
+    }
+    return copysignf(q, f);
+}
+
+/* what K or V becomes on entering the cache, as a bf16 pattern */
+static uint16_t kv_round(const orc_config *c, float f) {
+    return c->kv_fp8 ? orc_f32_to_bf16(orc_e4m3_round(f)) : orc_f32_to_bf16(f);
 }
 
 /* ---- the elementary operations ---------------------------------------------------------- */
@@ -148,8 +179,10 @@ void orc_kv_fill(const orc_config *c, uint16_t *kpool, uint16_t *vpool, const ui
             int p = t - seq_start[b];
             int32_t blk = block_table[(size_t)b * max_blocks + p / c->block_size];
             size_t at = kv_index(c, blk, p % c->block_size, 0);
-            memcpy(kpool + at, k + (size_t)t * row, row * 2);
-            memcpy(vpool + at, v + (size_t)t * row, row * 2);
+            for (size_t j = 0; j < row; ++j) {   /* bf16 values pass unchanged unless the cache is 8-bit */
+                kpool[at + j] = kv_round(c, orc_bf16_to_f32(k[(size_t)t * row + j]));
+                vpool[at + j] = kv_round(c, orc_bf16_to_f32(v[(size_t)t * row + j]));
+            }
         }
 }
 
@@ -210,8 +243,8 @@ void orc_layer_step(const orc_config *c, const orc_layer *w, float *x, int pos, 
         for (int h = 0; h < nkv; ++h) {
             size_t at = kv_index(c, blk, slot, h);
             for (int j = 0; j < d; ++j) {
-                kpool[at + j] = orc_f32_to_bf16(k[h * d + j]);
-                vpool[at + j] = orc_f32_to_bf16(v[h * d + j]);
+                kpool[at + j] = kv_round(c, k[h * d + j]);
+                vpool[at + j] = kv_round(c, v[h * d + j]);
             }
         }
     }
@@ -309,8 +342,8 @@ void orc_full_causal(const orc_config *c, const orc_weights *w, const int32_t *t
             for (int h = 0; h < nkv; ++h) orc_rope(qkv + QD + h * d, d, t, c->rope_theta);
             for (int i = 0; i < QD; ++i) Q[(size_t)t * QD + i] = round_act(c, qkv[i]);
             for (int i = 0; i < KD; ++i) {
-                Km[(size_t)t * KD + i] = round_act(c, qkv[QD + i]);
-                Vm[(size_t)t * KD + i] = round_act(c, qkv[QD + KD + i]);
+                Km[(size_t)t * KD + i] = c->kv_fp8 ? orc_e4m3_round(qkv[QD + i]) : round_act(c, qkv[QD + i]);
+                Vm[(size_t)t * KD + i] = c->kv_fp8 ? orc_e4m3_round(qkv[QD + KD + i]) : round_act(c, qkv[QD + KD + i]);
             }
         }
         for (int t = 0; t < n; ++t) {
