@@ -39,7 +39,7 @@ def measured_traffic(workload_name):
     return PMC_TRAFFIC["fetch_bytes"] + PMC_TRAFFIC["write_bytes"]
 
 
-def cpu_baseline(wl, dw_host, sample_rows, sample_layers):
+def cpu_baseline(wl, dw_host, sample_rows, sample_layers, kv_fp8=False):
     """Time the CPU oracle, as it stands, on a bounded sample of the same workload: `sample_rows`
     sequences through `sample_layers` layers plus embedding and LM head, then scale the per-layer
     time to the full depth.  Returns the JSON object."""
@@ -51,7 +51,7 @@ def cpu_baseline(wl, dw_host, sample_rows, sample_layers):
     s = wl.shape
     rows = dw_host["rows"]
     sub = dataclasses.replace(s, n_layers=sample_layers)
-    cfg = oracle.make_config(sub)
+    cfg = oracle.make_config(sub, kv_fp8=kv_fp8)
     w = oracle.Weights(dw_host["globals"], dw_host["layers"])
     ctx, table = dw_host["ctx"][rows], dw_host["table_rows"]
     kv = oracle.PagedKV(cfg, dw_host["num_blocks"])
@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--weight-swap", action="store_true",
                     help="instead of decode steps, time re-packing a whole policy version (hx_weights_pack of every tensor, "
                          "sources resident on the GPU) into the live engine")
+    ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
+                    help="element type of the KV cache: bf16 (the contract the headline metric is quoted on) or the "
+                         "8-bit E4M3 variant (reported as such; its CPU baseline runs the oracle's 8-bit variant)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this size (5 launches): the known traffic against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of a profiler run are scaled")
@@ -199,7 +202,8 @@ def main():
         return
 
     t_build = time.perf_counter()
-    dw = workload.build(wl, tap=tap)
+    fp8 = args.kv_dtype == "fp8"
+    dw = workload.build(wl, tap=tap, kv_dtype=binding.HX_KV_FP8_E4M3 if fp8 else binding.HX_KV_BF16)
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t_build
     eng = dw.engine
@@ -269,13 +273,15 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
                    "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves(),
+                   "kv_cache": "fp8-e4m3" if fp8 else "bf16",
                    "token_choice": ("sample T=%g%s + logprob" % (args.sample, " top-p %g" % args.top_p if args.top_p < 1 else ""))
                    if args.sample > 0 else "greedy"},
         "step_hbm": {"algorithmic_bytes": nbytes["total"], "weights_bytes": nbytes["weights"], "kv_bytes": nbytes["kv"],
                      "achieved_GBps": nbytes["total"] / (dt / args.steps) / 1e9,
                      "frac_of_peak": nbytes["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"kernel": "attn_splitk_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
+        "roofline": {"kernel": "attn_splitk_fp8_kernel" if fp8 else "attn_splitk_kernel", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None if fp8 else measured_traffic(wl.name),
                      "traffic_unit": "bytes per launch",
                      "launches_timed": int(attn_n), "avg_launch_ms": attn_avg_ms,
                      "algorithmic_bytes_per_launch": kv_bytes_per_launch},
@@ -295,7 +301,7 @@ def main():
         out["breakdown"] = bd
 
     if host is not None:
-        out["cpu_baseline"] = cpu_baseline(wl, host, args.cpu_rows, args.cpu_layers)
+        out["cpu_baseline"] = cpu_baseline(wl, host, args.cpu_rows, args.cpu_layers, kv_fp8=fp8)
         out["cpu_baseline"]["gpu_over_cpu"] = tokens_per_s / out["cpu_baseline"]["value"]
     print(json.dumps(out))
 

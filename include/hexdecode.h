@@ -59,7 +59,16 @@ typedef struct {
     float rope_theta;
     int32_t max_batch;    /* 1..256 sequences per decode step                        */
     int32_t max_seq_len;  /* largest KV length (new token included) of any sequence  */
+    int32_t kv_dtype;     /* HX_KV_BF16 or HX_KV_FP8_E4M3: element type of the KV cache */
 } hx_model_config;
+
+/* Element type of the paged KV cache.  HX_KV_BF16 is the numeric contract of the decode step.  HX_KV_FP8_E4M3 is a
+   variant that halves the bytes the attention kernel streams: K (after RoPE) and V are rounded from fp32 straight to
+   the 8-bit format E4M3 of the OCP 8-bit floating point specification (bias 7, largest finite value 448, no
+   infinities), nearest-even, magnitudes above 448 saturating, with no scale factor; attention converts them back
+   exactly (every E4M3 value is a bf16 value) and proceeds as in the bf16 contract.  prefill_fill rounds the
+   caller's bf16 K/V the same way and hx_kv_gather returns the stored values as bf16. */
+enum { HX_KV_BF16 = 0, HX_KV_FP8_E4M3 = 1 };
 
 typedef enum {
     HX_OK = 0,

@@ -34,7 +34,10 @@ class ModelConfig(C.Structure):
     _fields_ += [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
                                           "intermediate", "vocab", "block_size", "qkv_bias")]
     _fields_ += [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_batch", C.c_int32),
-                 ("max_seq_len", C.c_int32)]
+                 ("max_seq_len", C.c_int32), ("kv_dtype", C.c_int32)]
+
+
+HX_KV_BF16, HX_KV_FP8_E4M3 = 0, 1
 
 
 class HexError(RuntimeError):
@@ -112,11 +115,11 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_config(shape, max_batch: int, max_seq_len: int) -> ModelConfig:
+def make_config(shape, max_batch: int, max_seq_len: int, kv_dtype: int = HX_KV_BF16) -> ModelConfig:
     """hx_model_config from any object with the ModelShape field names."""
     return ModelConfig(C.sizeof(ModelConfig), shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads,
                        shape.head_dim, shape.intermediate, shape.vocab, shape.block_size,
-                       1 if shape.qkv_bias else 0, shape.rms_eps, shape.rope_theta, max_batch, max_seq_len)
+                       1 if shape.qkv_bias else 0, shape.rms_eps, shape.rope_theta, max_batch, max_seq_len, kv_dtype)
 
 
 def weights_bytes(cfg: ModelConfig) -> int:
@@ -140,9 +143,9 @@ def kv_bytes(cfg: ModelConfig, num_blocks: int) -> int:
 class Engine:
     """hx_engine plus the torch-owned device buffers it wraps."""
 
-    def __init__(self, shape, max_batch: int, max_seq_len: int, device="cuda:0"):
+    def __init__(self, shape, max_batch: int, max_seq_len: int, device="cuda:0", kv_dtype: int = HX_KV_BF16):
         self.shape = shape
-        self.cfg = make_config(shape, max_batch, max_seq_len)
+        self.cfg = make_config(shape, max_batch, max_seq_len, kv_dtype)
         self.device = torch.device(device)
         self.weights = torch.empty(weights_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)

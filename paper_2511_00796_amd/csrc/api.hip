@@ -49,6 +49,8 @@ static int check_config(const hx_model_config *c) {
     if (c->max_batch < 1 || c->max_batch > 256) return hx_fail(HX_E_CONFIG, "max_batch %d not in [1, 256]", c->max_batch);
     if (c->max_seq_len < 1 || c->max_seq_len > (1 << 20)) return hx_fail(HX_E_CONFIG, "max_seq_len %d not in [1, 2^20]", c->max_seq_len);
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return hx_fail(HX_E_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
+    if (c->kv_dtype != HX_KV_BF16 && c->kv_dtype != HX_KV_FP8_E4M3)
+        return hx_fail(HX_E_CONFIG, "kv_dtype %d: HX_KV_BF16 or HX_KV_FP8_E4M3", c->kv_dtype);
     return HX_OK;
 }
 
@@ -152,7 +154,7 @@ static int init_engine_shape(hx_engine *e, const hx_model_config *cfg) {
     e->attn_waves = attention_waves();
     // HX_CHUNK_ATTENTION=0: prompt rows go through the decode step's attention, one K/V stream per row (comparison)
     const char *ca = getenv("HX_CHUNK_ATTENTION");
-    e->chunk_attention = e->G <= HX_CHUNK_ROWS && !(ca && atoi(ca) == 0);
+    e->chunk_attention = e->G <= HX_CHUNK_ROWS && !(ca && atoi(ca) == 0) && cfg->kv_dtype == HX_KV_BF16;
     return HX_OK;
 }
 
@@ -180,7 +182,8 @@ extern "C" int hx_kv_bytes(const hx_model_config *cfg, int64_t num_blocks, size_
     int rc = check_config(cfg);
     if (rc) return rc;
     if (num_blocks < 1 || num_blocks > (int64_t)0x7fffffff) return hx_fail(HX_E_RANGE, "num_blocks %lld out of range", (long long)num_blocks);
-    *out = (size_t)cfg->n_layers * (size_t)num_blocks * cfg->n_kv_heads * 2 * (16 * (size_t)cfg->head_dim * 2);
+    const size_t elem = cfg->kv_dtype == HX_KV_FP8_E4M3 ? 1 : 2;
+    *out = (size_t)cfg->n_layers * (size_t)num_blocks * cfg->n_kv_heads * 2 * (16 * (size_t)cfg->head_dim * elem);
     return HX_OK;
 }
 
@@ -290,7 +293,8 @@ extern "C" int kv_alloc(hx_engine *e, void *kv_dev, size_t kv_bytes, int64_t num
     kv->engine = e;
     kv->pool = (char *)kv_dev;
     kv->num_blocks = num_blocks;
-    kv->tile_bytes = 16 * (size_t)e->D * 2;
+    kv->fp8 = e->cfg.kv_dtype == HX_KV_FP8_E4M3;
+    kv->tile_bytes = 16 * (size_t)e->D * (kv->fp8 ? 1 : 2);
     kv->block_bytes = (size_t)e->cfg.n_kv_heads * 2 * kv->tile_bytes;
     kv->layer_bytes = (size_t)num_blocks * kv->block_bytes;
     *out = kv;
@@ -418,7 +422,8 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
             HX_TIMED(HX_K_ATTENTION, hx_launch_chunk_attention(e, kv, l, block_table, max_blocks, st));
             HX_TIMED(HX_K_COMBINE, hx_launch_chunk_combine(e, batch, capture, st));
         } else {
-            HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
+            if (kv->fp8) HX_TIMED(HX_K_ATTENTION, hx_launch_attention_fp8(e, kv, l, block_table, max_blocks, st));
+            else HX_TIMED(HX_K_ATTENTION, hx_launch_attention(e, kv, l, batch, seq_lens, block_table, max_blocks, st));
             HX_TIMED(HX_K_COMBINE, hx_launch_combine(e, batch, capture, st));
         }
         HX_TIMED(HX_K_GEMM_O, hx_launch_gemm(e, &lm->wo, batch, ws + e->map.ap, HX_EPI_PARTIAL, ypart, nullptr, st));
@@ -591,7 +596,9 @@ extern "C" int hx_stage_attention(hx_engine *e, hx_kv *kv, int layer, int32_t ba
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hx_launch_pack_q(e, batch, q_dev, st))) return rc;
     if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
-    if ((rc = hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, st))) return rc;
+    if (kv->fp8) rc = hx_launch_attention_fp8(e, kv, layer, block_table, max_blocks, st);
+    else rc = hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, st);
+    if (rc) return rc;
     return hx_launch_combine(e, batch, out_dev, st);
 }
 

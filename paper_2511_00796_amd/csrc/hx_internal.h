@@ -59,6 +59,26 @@ int hx_fail(int code, const char *fmt, ...);
 // ---- small device helpers ------------------------------------------------------------------------
 __device__ __forceinline__ float hx_bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
+// fp32 -> E4M3 (nearest even; the conversion instruction of gfx950 follows the OCP format), saturating at +-448:
+// 8 values into 8 bytes, value j in byte j
+__device__ __forceinline__ uint2 hx_pack8_e4m3(const float *v) {
+    float c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = fminf(fmaxf(v[j], -448.0f), 448.0f);
+    int w0 = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], 0, false);
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], w0, true);
+    int w1 = __builtin_amdgcn_cvt_pk_fp8_f32(c[4], c[5], 0, false);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(c[6], c[7], w1, true);
+    return make_uint2((uint32_t)w0, (uint32_t)w1);
+}
+// 4 E4M3 bytes of one dword -> 4 bf16 (exact), byte j -> element j
+typedef __bf16 hx_bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 hx_e4m3x4_to_bf16x4(uint32_t w) {
+    const hx_bf16x2_t lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+    const hx_bf16x2_t hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
+    return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+}
+
 // round-to-nearest-even on the upper half of the fp32 pattern (finite inputs)
 __device__ __forceinline__ uint16_t hx_f32_to_bf16(float f) {
     uint32_t u = __float_as_uint(f);
@@ -96,6 +116,16 @@ __host__ __device__ __forceinline__ int hx_ktile_index(int t, int d) {
 }
 __host__ __device__ __forceinline__ int hx_vtile_index(int t, int d) {
     return (d >> 5) * 512 + ((((t >> 2) * 16) + (d & 15)) << 3) + (((d >> 4) & 1) << 2) + (t & 3);
+}
+
+// The same tiles with 1-byte elements (8-bit cache): the 8 bytes a lane holds for operand step 2p and the 8 it holds
+// for step 2p + 1 sit side by side, so that one 16-byte load per lane (1 KiB per wavefront) fetches two steps:
+//   byte index = (step / 2) * 1024 + lane * 16 + (step % 2) * 8 + (byte within the lane's 8), lane and byte as above.
+__host__ __device__ __forceinline__ int hx_ktile8_index(int t, int d) {
+    return (d >> 6) * 1024 + ((((d >> 3) & 3) * 16 + t) << 4) + (((d >> 5) & 1) << 3) + (d & 7);
+}
+__host__ __device__ __forceinline__ int hx_vtile8_index(int t, int d) {
+    return (d >> 6) * 1024 + ((((t >> 2) * 16) + (d & 15)) << 4) + (((d >> 5) & 1) << 3) + (((d >> 4) & 1) << 2) + (t & 3);
 }
 
 // ---- host-side descriptors ------------------------------------------------------------------------
@@ -156,7 +186,8 @@ struct hx_kv {
     hx_engine *engine;
     char *pool;             // device
     int64_t num_blocks;
-    size_t tile_bytes;      // 16 * head_dim * 2
+    bool fp8;               // 8-bit (E4M3) elements
+    size_t tile_bytes;      // 16 * head_dim * element size
     size_t block_bytes;     // n_kv_heads * 2 * tile_bytes
     size_t layer_bytes;     // num_blocks * block_bytes
 };
@@ -213,6 +244,10 @@ int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_len
 int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
                               hipStream_t st);
 int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st);
+
+// attention_fp8.hip: the decode step's attention over an 8-bit cache
+int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
+                            hipStream_t st);
 
 // sampling.hip
 int hx_launch_nucleus(const hx_engine *e, int batch, const float *logits, const hx_sample_params *sample,

@@ -6,7 +6,7 @@
 // ---- prefill_fill / hx_kv_gather ---------------------------------------------------------------------
 // One 64-thread group per (token, kv_head): each thread moves 16 bytes of K and 16 bytes of V
 // (head_dim 128: 8 bf16 x 16 threads ... all 64 threads busy over K and V halves).
-template <int D, bool GATHER>
+template <int D, bool GATHER, bool FP8>
 __global__ __launch_bounds__(256) void kv_scatter_kernel(char *pool_layer, size_t block_bytes, size_t tile_bytes,
                                                          uint16_t *k_log, uint16_t *v_log,
                                                          const int32_t *__restrict__ seq_start,
@@ -32,6 +32,33 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(char *pool_layer, size_
     uint16_t *ktile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes);
     uint16_t *vtile = (uint16_t *)((char *)ktile + tile_bytes);
     size_t src = ((size_t)tok * n_kv + kvh) * D + c * 8;
+    if (FP8) {
+        // 8-bit cache: bf16 <-> E4M3 on the way (rounding on the way in, exact on the way out)
+        uint8_t *k8 = (uint8_t *)ktile, *v8 = (uint8_t *)vtile;
+        if (!GATHER) {
+            const uint4 kk = *(const uint4 *)(k_log + src), vv = *(const uint4 *)(v_log + src);
+            const uint16_t *ke = (const uint16_t *)&kk, *ve = (const uint16_t *)&vv;
+            float kf[8], vf[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { kf[j] = hx_bf16_to_f32(ke[j]); vf[j] = hx_bf16_to_f32(ve[j]); }
+            *(uint2 *)(k8 + hx_ktile8_index(slot, c * 8)) = hx_pack8_e4m3(kf);
+            const uint2 vp = hx_pack8_e4m3(vf);
+            const uint8_t *vb = (const uint8_t *)&vp;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v8[hx_vtile8_index(slot, c * 8 + j)] = vb[j];
+        } else {
+            const uint2 kp = *(const uint2 *)(k8 + hx_ktile8_index(slot, c * 8));
+            const uint2 k03 = hx_e4m3x4_to_bf16x4(kp.x), k47 = hx_e4m3x4_to_bf16x4(kp.y);
+            *(uint4 *)(k_log + src) = make_uint4(k03.x, k03.y, k47.x, k47.y);
+            uint2 vp;
+            uint8_t *vb = (uint8_t *)&vp;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vb[j] = v8[hx_vtile8_index(slot, c * 8 + j)];
+            const uint2 v03 = hx_e4m3x4_to_bf16x4(vp.x), v47 = hx_e4m3x4_to_bf16x4(vp.y);
+            *(uint4 *)(v_log + src) = make_uint4(v03.x, v03.y, v47.x, v47.y);
+        }
+        return;
+    }
     if (!GATHER) {
         uint4 kk = *(const uint4 *)(k_log + src);
         *(uint4 *)(ktile + hx_ktile_index(slot, c * 8)) = kk;      // 8 consecutive d stay together in a K tile
@@ -60,12 +87,18 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
     if (blocks > 0x7fffffffLL) return hx_fail(HX_E_RANGE, "total_tokens too large for one launch");
     char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     dim3 grid((unsigned)blocks), block(256);
-#define HX_KV_LAUNCH(DD, GG)                                                                                   \
-    hipLaunchKernelGGL((kv_scatter_kernel<DD, GG>), grid, block, 0, st, pool_layer, kv->block_bytes,          \
+#define HX_KV_LAUNCH(DD, GG, F8)                                                                               \
+    hipLaunchKernelGGL((kv_scatter_kernel<DD, GG, F8>), grid, block, 0, st, pool_layer, kv->block_bytes,      \
                        kv->tile_bytes, (uint16_t *)k, (uint16_t *)v, seq_start, table, max_blocks, batch,     \
                        total_tokens, n_kv)
-    if (D == 128) { if (gather) HX_KV_LAUNCH(128, true); else HX_KV_LAUNCH(128, false); }
-    else          { if (gather) HX_KV_LAUNCH(64, true);  else HX_KV_LAUNCH(64, false); }
+#define HX_KV_LAUNCH_D(DD)                                                                                     \
+    do {                                                                                                       \
+        if (kv->fp8) { if (gather) HX_KV_LAUNCH(DD, true, true); else HX_KV_LAUNCH(DD, false, true); }        \
+        else         { if (gather) HX_KV_LAUNCH(DD, true, false); else HX_KV_LAUNCH(DD, false, false); }      \
+    } while (0)
+    if (D == 128) HX_KV_LAUNCH_D(128);
+    else          HX_KV_LAUNCH_D(64);
+#undef HX_KV_LAUNCH_D
 #undef HX_KV_LAUNCH
     HX_CHECK_LAUNCH("kv_scatter");
     return HX_OK;
@@ -74,13 +107,14 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
 // ---- bias + RoPE + append -------------------------------------------------------------------------------
 // The q/k/v projection arrives as `splits` fp32 partial results [split][batch][qkv_dim] (summed here in
 // split order), the bias is added, q and k heads are rotated by the position's angles (pairs (i, i + D/2)),
-// q is written as the packed bf16 B operand of the attention kernel, k and v are rounded to bf16 and stored
+// q is written as the packed bf16 B operand of the attention kernel, k and v are rounded to bf16 (or, for an 8-bit
+// cache, from fp32 straight to E4M3) and stored
 // at (block_table[b][pos/16], pos%16).
 // One thread per work item of 16 values: for q and k heads, 8 consecutive d of the lower half and the 8
 // matching d of the upper half (both ends of the rotation, two 16-byte stores); for v, 16 consecutive d.
 // grid (batch, ceil(items / 128)), 128 threads.  Query rows g >= G of the packed operand are never written:
 // they only feed accumulator columns that nobody reads.
-template <int D>
+template <int D, bool FP8>
 __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restrict__ ypart, int splits,
                                                           size_t split_stride, const uint16_t *__restrict__ bias,
                                                           int has_bias, const float *__restrict__ cs,
@@ -154,9 +188,14 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
             *(uint4 *)(dst + (d1 >> 5) * 512 + ((((d1 >> 3) & 3) * 16 + g) << 3)) = pack8(r1);
         } else {
             const int kvh = head - n_q;
-            uint16_t *ktile = (uint16_t *)(pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes);
-            *(uint4 *)(ktile + hx_ktile_index(slot, i0)) = pack8(r0);
-            *(uint4 *)(ktile + hx_ktile_index(slot, i0 + HALF)) = pack8(r1);
+            char *ktile = pool_layer + (size_t)blk * block_bytes + (size_t)kvh * 2 * tile_bytes;
+            if (FP8) {                                     // 8-bit cache: fp32 -> E4M3 directly
+                *(uint2 *)(ktile + hx_ktile8_index(slot, i0)) = hx_pack8_e4m3(r0);
+                *(uint2 *)(ktile + hx_ktile8_index(slot, i0 + HALF)) = hx_pack8_e4m3(r1);
+            } else {
+                *(uint4 *)((uint16_t *)ktile + hx_ktile_index(slot, i0)) = pack8(r0);
+                *(uint4 *)((uint16_t *)ktile + hx_ktile_index(slot, i0 + HALF)) = pack8(r1);
+            }
         }
     } else {
         const int vi = item - rot_items;
@@ -166,8 +205,15 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             gather8((n_q + n_kv) * D + kvh * D + d0 + 8 * h, v);
+            if (FP8) {
+                const uint2 vp = hx_pack8_e4m3(v);
+                const uint8_t *vb = (const uint8_t *)&vp;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vtile[hx_vtile_index(slot, d0 + 8 * h + j)] = hx_f32_to_bf16(v[j]);
+                for (int j = 0; j < 8; ++j) ((uint8_t *)vtile)[hx_vtile8_index(slot, d0 + 8 * h + j)] = vb[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) vtile[hx_vtile_index(slot, d0 + 8 * h + j)] = hx_f32_to_bf16(v[j]);
+            }
         }
     }
 }
@@ -182,14 +228,13 @@ int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int ba
     uint16_t *qp = (uint16_t *)(e->ws + e->map.qp);
     const int items = (e->cfg.n_q_heads + e->cfg.n_kv_heads) * (e->D / 16) + e->cfg.n_kv_heads * (e->D / 16);
     dim3 grid(batch, (items + 127) / 128), block(128);
-    if (e->D == 128)
-        hipLaunchKernelGGL((rope_append_kernel<128>), grid, block, 0, st, ypart, splits, split_stride, bias,
-                           e->cfg.qkv_bias, cs, positions, table, max_blocks, pool_layer, kv->block_bytes,
-                           kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch);
-    else
-        hipLaunchKernelGGL((rope_append_kernel<64>), grid, block, 0, st, ypart, splits, split_stride, bias,
-                           e->cfg.qkv_bias, cs, positions, table, max_blocks, pool_layer, kv->block_bytes,
-                           kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch);
+#define HX_ROPE_LAUNCH(DD, F8)                                                                                  \
+    hipLaunchKernelGGL((rope_append_kernel<DD, F8>), grid, block, 0, st, ypart, splits, split_stride, bias,    \
+                       e->cfg.qkv_bias, cs, positions, table, max_blocks, pool_layer, kv->block_bytes,         \
+                       kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch)
+    if (e->D == 128) { if (kv->fp8) HX_ROPE_LAUNCH(128, true); else HX_ROPE_LAUNCH(128, false); }
+    else             { if (kv->fp8) HX_ROPE_LAUNCH(64, true);  else HX_ROPE_LAUNCH(64, false); }
+#undef HX_ROPE_LAUNCH
     HX_CHECK_LAUNCH("rope_append");
     return HX_OK;
 }

@@ -220,11 +220,12 @@ def kv_fill(shape: ModelShape, layer: int, total_tokens: int, seed: int, device=
     return k, v
 
 
-def algorithmic_bytes(shape: ModelShape, seq_lens: np.ndarray) -> Dict[str, int]:
+def algorithmic_bytes(shape: ModelShape, seq_lens: np.ndarray, kv_elem_bytes: int = 2) -> Dict[str, int]:
     """Bytes a decode step must move: every streamed weight once plus the K and V of every
-    attended position (``seq_lens`` = keys attended per sequence, new token included)."""
+    attended position (``seq_lens`` = keys attended per sequence, new token included).
+    ``kv_elem_bytes``: 2 for the bf16 cache, 1 for the 8-bit variant."""
     w = 2 * shape.weight_elements()
-    kv = int(np.asarray(seq_lens, dtype=np.int64).sum()) * shape.kv_bytes_per_token()
+    kv = int(np.asarray(seq_lens, dtype=np.int64).sum()) * shape.kv_bytes_per_token() * kv_elem_bytes // 2
     return {"weights": w, "kv": kv, "total": w + kv}
 
 

@@ -40,16 +40,19 @@ class DeviceWorkload:
                                 self.logits if with_logits else None, self.next_tokens)
 
     def bytes(self):
-        return synth.algorithmic_bytes(self.wl.shape, self.seq_lens)
+        return synth.algorithmic_bytes(self.wl.shape, self.seq_lens,
+                                       1 if self.engine.cfg.kv_dtype == binding.HX_KV_FP8_E4M3 else 2)
 
 
 def build(wl: synth.Workload, device="cuda:0", n_layers: Optional[int] = None,
-          tap: Optional[Callable[[str, int, dict], None]] = None, max_seq_len: Optional[int] = None) -> DeviceWorkload:
+          tap: Optional[Callable[[str, int, dict], None]] = None, max_seq_len: Optional[int] = None,
+          kv_dtype: int = binding.HX_KV_BF16) -> DeviceWorkload:
     """Build the engine and a cache pre-filled with N(0,1) K/V for ``wl`` (kv_fill == "normal").
 
     ``n_layers`` truncates the model (parity tests on mid-size cases).  ``tap(kind, layer, tensors)``
     is called with kind "layer" (weights dict), "kv" ({"k", "v"} of that layer, logical layout) and
-    "globals" (first) while the device tensors are alive.
+    "globals" (first) while the device tensors are alive.  ``kv_dtype``: element type of the cache (the bf16
+    K/V handed to prefill_fill are rounded to it by the library).
     """
     shape = wl.shape
     if n_layers is not None:
@@ -62,7 +65,7 @@ def build(wl: synth.Workload, device="cuda:0", n_layers: Optional[int] = None,
     seq_start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
     total = int(ctx.sum())
     msl = int(seq_lens.max()) if max_seq_len is None else max_seq_len
-    eng = binding.Engine(shape, wl.batch, msl, device=device)
+    eng = binding.Engine(shape, wl.batch, msl, device=device, kv_dtype=kv_dtype)
     kv = binding.KVCache(eng, num_blocks)
     table_d = torch.from_numpy(table).to(dev)
     start_d = torch.from_numpy(seq_start).to(dev)

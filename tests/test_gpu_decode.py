@@ -283,20 +283,21 @@ def test_decode_step_can_be_captured_in_a_graph(hx):
         assert torch.equal(dw.logits, ref_logits), i
 
 
-def run_sampled(hx, wl, n_layers, rows, with_floor=False):
+def run_sampled(hx, wl, n_layers, rows, with_floor=False, kv_fp8=False):
+    """kv_fp8: the 8-bit cache variant on both sides."""
     from paper_2511_00796_amd import workload
     shape = wl.shape if n_layers is None else dataclasses.replace(wl.shape, n_layers=n_layers)
     ctx = synth.context_lengths(wl)
     seq_start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int64)
     tokens = synth.token_ids(wl, wl.batch)
-    orc = OracleRows(shape, rows, ctx, seq_start, tokens)
-    alt = OracleRows(shape, rows, ctx, seq_start, tokens, descending=True) if with_floor else None
+    orc = OracleRows(shape, rows, ctx, seq_start, tokens, kv_fp8=kv_fp8)
+    alt = OracleRows(shape, rows, ctx, seq_start, tokens, descending=True, kv_fp8=kv_fp8) if with_floor else None
 
     def tap(kind, layer, t):
         orc.tap(kind, layer, t)
         if alt:
             alt.tap(kind, layer, t)
-    dw = workload.build(wl, n_layers=n_layers, tap=tap)
+    dw = workload.build(wl, n_layers=n_layers, tap=tap, kv_dtype=hx.HX_KV_FP8_E4M3 if kv_fp8 else hx.HX_KV_BF16)
     orc.finish()
     cap = torch.empty(shape.n_layers, wl.batch, shape.q_dim, dtype=torch.float32, device="cuda")
     dw.engine.set_attn_capture(cap)

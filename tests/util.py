@@ -34,12 +34,12 @@ class OracleRows:
     paper_2511_00796_amd.workload.build).  Rows are independent in the decode step, so the sampled
     rows' results are exactly what the full-batch oracle would give for them."""
 
-    def __init__(self, shape, rows, ctx, seq_start, tokens, descending=False):
+    def __init__(self, shape, rows, ctx, seq_start, tokens, descending=False, kv_fp8=False):
         from concurrent.futures import ThreadPoolExecutor
         self.shape, self.rows = shape, list(rows)
         self.descending = descending          # run the equally valid descending-k variant of the oracle
         self.ctx, self.seq_start, self.tokens = ctx, seq_start, tokens
-        self.cfg1 = oracle.make_config(shape)
+        self.cfg1 = oracle.make_config(shape, kv_fp8=kv_fp8)   # kv_fp8: the 8-bit cache variant
         self.cfg1.n_layers = 1
         self.pool = ThreadPoolExecutor(max_workers=min(len(self.rows), 16))
         self.x = {}
