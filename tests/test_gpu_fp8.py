@@ -181,3 +181,43 @@ def test_full_size_7b_batch_128_with_8_bit_cache(hx):
     print("7b-b128, 8-bit cache, rows %s: logit err / max|logit| %.3e, attn err %.3e, strict agreement %.4f" % ((rows,) + res))
     del dw
     torch.cuda.empty_cache()
+
+
+def test_prompt_chunks_fill_the_8_bit_cache(hx):
+    """Config-1 prompts through prefill_chunk (48 interleaved rows per call) into an 8-bit cache, the last prompt
+    token through decode_step: logits against the oracle's dense causal recomputation with the 8-bit rounding."""
+    wl = synth.WORKLOADS["tiny-b4"]
+    s = wl.shape
+    ow, g, layers = host_model(s, wl.seed)
+    cfg = oracle.make_config(s, kv_fp8=True)
+    ctx = synth.context_lengths(wl)
+    table, nb = synth.block_table(ctx + 1, s.block_size, wl.seed)
+    prompts = [synth.token_ids(wl, int(ctx[b]), salt=b) for b in range(wl.batch)]
+    eng = hx.Engine(s, 48, int(ctx.max()) + 1, kv_dtype=hx.HX_KV_FP8_E4M3)
+    for l in range(s.n_layers):
+        eng.pack_layer(l, synth.layer_weights(s, l, wl.seed))
+    eng.pack_globals(synth.global_weights(s, wl.seed))
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    rows = [(b, p) for p in range(int(ctx.max())) for b in range(wl.batch) if p < ctx[b] - 1]
+    for at in range(0, len(rows), 48):
+        chunk = rows[at:at + 48]
+        bs = np.array([b for b, _ in chunk])
+        ps = np.array([p for _, p in chunk], dtype=np.int32)
+        toks = np.array([prompts[b][p] for b, p in chunk], dtype=np.int32)
+        eng.prefill_chunk(kv, dev(toks), dev(ps), dev(ps + 1), dev(table[bs]))
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[b][-1] for b in range(wl.batch)], dtype=np.int32)
+    logits = torch.empty(wl.batch, s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(wl.batch, dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    worst = 0.0
+    for b in range(wl.batch):
+        ref = oracle.full_causal(cfg, ow, prompts[b])[0][-1]
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(gl[b] - ref).max())
+        assert err <= LOGIT_TOL * scale, (b, err, scale)
+        worst = max(worst, err / scale)
+    print("prompt chunks, 8-bit cache: worst logit err / max|logit| %.3e" % worst)
