@@ -114,11 +114,12 @@ __global__ __launch_bounds__(256) void chunk_setup_kernel(int n_rows, int n_kv, 
 }
 
 // ---- the attention kernel ---------------------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void load_tile_c(u32x4_t (&r)[D / 16], const char *tile, int lane) {
+// loads of 1 KiB per tile: D/16 for bf16 elements, D/32 for the 8-bit cache (tile layouts: hx_internal.h)
+template <int NL>
+__device__ __forceinline__ void load_tile_c(u32x4_t (&r)[NL], const char *tile, int lane) {
     const u32x4_t *p = (const u32x4_t *)tile + lane;
 #pragma unroll
-    for (int i = 0; i < D / 16; ++i) r[i] = __builtin_nontemporal_load(p + i * 64);
+    for (int i = 0; i < NL; ++i) r[i] = __builtin_nontemporal_load(p + i * 64);
 }
 
 template <int D>
@@ -132,7 +133,7 @@ struct ChunkState {
 // the lane's column of block cb attends (0 for an unused column), t_first / t_last = the smallest and largest of the
 // used ones, n_cb = column blocks in use.  qs = this wavefront's staged query operands.  Ring and load stream as in
 // the decode kernel.
-template <int D, int PF>
+template <int D, int PF, bool FP8>
 __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x4_t *qs, const char *pool_layer,
                                                    size_t block_bytes, size_t head_off, const char *qtile,
                                                    int32_t blk_lo, int32_t blk_hi, int nblk, int t0,
@@ -145,11 +146,12 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
     int t1c[HX_CHUNK_CB];
 #pragma unroll
     for (int cb = 0; cb < HX_CHUNK_CB; ++cb) t1c[cb] = min(tcol[cb], t_end);
-    u32x4_t ring[PF][D / 16];
+    constexpr int NL = FP8 ? D / 32 : D / 16;
+    u32x4_t ring[PF][NL];
 #pragma unroll
     for (int s = 0; s < PF; ++s)
 #pragma unroll
-        for (int i = 0; i < D / 16; ++i) ring[s][i] = u32x4_t{0u, 0u, 0u, 0u};
+        for (int i = 0; i < NL; ++i) ring[s][i] = u32x4_t{0u, 0u, 0u, 0u};
 
     const int n_rounds = (nblk + PF - 1) / PF + 1;
     for (int rd = 0; rd < n_rounds; ++rd) {
@@ -158,15 +160,39 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
             const int i = (rd - 1) * PF + s;                   // tile of this iteration; < 0 while the ring fills
             const int tok0 = t0 + i * 16 + qd * 4;             // this lane's 4 tokens
             const bool edge = i < 0 || t0 + (i + 1) * 16 > t_clean;   // wave-uniform
-            u32x4_t vv[D / 32];
+            // operands of this tile: K steps kop[kk], V steps vv[q] (x, y: rows d < 16 of the step; z, w: rows d >= 16).
+            // V of positions that do not exist must not reach the product (it may hold anything, also NaN).
+            u32x4_t kop[D / 32], vv[D / 32];
+            const bool ragged = i < 0 || t0 + (i + 1) * 16 > t1v;     // wave-uniform
+            const int valid = (i < 0) ? 0 : (t1v - tok0);
+            if (FP8) {
+                // 8-bit cache: bytes -> bf16 (exact), once per tile for all column blocks
+                const uint32_t keep = (!ragged || valid >= 4) ? 0xffffffffu : (valid <= 0 ? 0u : ((1u << (8 * valid)) - 1u));
 #pragma unroll
-            for (int q = 0; q < D / 32; ++q) vv[q] = ring[s][D / 32 + q];
-            if (i < 0 || t0 + (i + 1) * 16 > t1v) {            // V of positions that do not exist must not reach the product
-                const int valid = (i < 0) ? 0 : (t1v - tok0);
-                const uint32_t m01 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
-                const uint32_t m23 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+                for (int kk = 0; kk < D / 32; ++kk) {
+                    const u32x4_t raw = ring[s][kk >> 1];
+                    const uint2 a = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.z : raw.x);
+                    const uint2 b = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.w : raw.y);
+                    kop[kk] = u32x4_t{a.x, a.y, b.x, b.y};
+                }
 #pragma unroll
-                for (int q = 0; q < D / 32; ++q) { vv[q].x &= m01; vv[q].y &= m23; vv[q].z &= m01; vv[q].w &= m23; }
+                for (int q = 0; q < D / 32; ++q) {
+                    const u32x4_t raw = ring[s][D / 64 + (q >> 1)];
+                    const uint2 lo = hx_e4m3x4_to_bf16x4(((q & 1) ? raw.z : raw.x) & keep);
+                    const uint2 hi = hx_e4m3x4_to_bf16x4(((q & 1) ? raw.w : raw.y) & keep);
+                    vv[q] = u32x4_t{lo.x, lo.y, hi.x, hi.y};
+                }
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) kop[kk] = ring[s][kk];
+#pragma unroll
+                for (int q = 0; q < D / 32; ++q) vv[q] = ring[s][D / 32 + q];
+                if (ragged) {
+                    const uint32_t m01 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+                    const uint32_t m23 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+                    for (int q = 0; q < D / 32; ++q) { vv[q].x &= m01; vv[q].y &= m23; vv[q].z &= m01; vv[q].w &= m23; }
+                }
             }
 #pragma unroll
             for (int cb = 0; cb < HX_CHUNK_CB; ++cb) {
@@ -174,7 +200,7 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
                 f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < D / 32; ++kk)
-                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ring[s][kk]),
+                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]),
                                                                  __builtin_bit_cast(bf16x8_t, qs[(cb * (D / 32) + kk) * 64 + lane]),
                                                                  sc, 0, 0, 0);
                 float s4[4];
@@ -226,7 +252,7 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
             const int nx = i + PF;
             const int32_t blk = (nx < 64) ? __builtin_amdgcn_readlane(blk_lo, nx & 63) : __builtin_amdgcn_readlane(blk_hi, nx & 63);
             const char *src = (nx < nblk) ? pool_layer + (size_t)blk * block_bytes + head_off : qtile;
-            load_tile_c<D>(ring[s], src, lane);
+            load_tile_c<NL>(ring[s], src, lane);
         }
     }
 }
@@ -234,7 +260,7 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
 // grid = wavefronts of the schedule, one wavefront per workgroup, at most 256 registers so that two wavefronts share a
 // SIMD and cover each other's latencies.  Partial result of run w and pair p = (group, KV
 // head): slot w + p, column block cb at sub-slot 4 * slot + cb: part_ml [sub][max 16 | sum 16], part_o [sub][16][D].
-template <int D, int PF>
+template <int D, int PF, bool FP8>
 __global__ __launch_bounds__(64, 2) void attn_chunk_kernel(const char *__restrict__ pool_layer, size_t block_bytes,
                                                         const uint16_t *__restrict__ qp,
                                                         const int32_t *__restrict__ table, int max_blocks,
@@ -279,7 +305,7 @@ __global__ __launch_bounds__(64, 2) void attn_chunk_kernel(const char *__restric
         const int kvh = local / nblk_g;
         const int blk0 = local - kvh * nblk_g;
         const int n = min(f1 - f, nblk_g - blk0);        // tiles of this pair in this run
-        const size_t head_off = (size_t)kvh * 2 * (16 * D * 2);
+        const size_t head_off = (size_t)kvh * 2 * (16 * D * (FP8 ? 1 : 2));   // K | V tiles of one head
         const int trow = first + rows - 1;               // the group reads the cache through its last row's table
         const int n_cb = (rows * G + 15) >> 4;           // column blocks in use
 
@@ -315,7 +341,7 @@ __global__ __launch_bounds__(64, 2) void attn_chunk_kernel(const char *__restric
             int32_t blk_hi = (64 + lane < nsub) ? row[64 + lane] : 0;
             const int t0 = (blk0 + done) * 16;
             asm volatile("" : "+v"(blk_lo), "+v"(blk_hi));
-            stream_tiles_chunk<D, PF>(st, qs, pool_layer, block_bytes, head_off, qtile, blk_lo, blk_hi, nsub, t0, tcol,
+            stream_tiles_chunk<D, PF, FP8>(st, qs, pool_layer, block_bytes, head_off, qtile, blk_lo, blk_hi, nsub, t0, tcol,
                                       n_cb, T - (rows - 1), T, scale_log2e, lane);
         }
 
@@ -432,8 +458,13 @@ int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, co
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), (const int32_t *)(ws + e->map.chunk_ginfo), e->cfg.n_kv_heads,     \
         e->G, scale_log2e, (float *)(ws + e->map.chunk_part_ml), (float *)(ws + e->map.chunk_part_o)
-    if (e->D == 128) hipLaunchKernelGGL((attn_chunk_kernel<128, 2>), grid, block, 0, st, HX_CHUNK_ARGS);
-    else             hipLaunchKernelGGL((attn_chunk_kernel<64, 3>), grid, block, 0, st, HX_CHUNK_ARGS);
+    if (kv->fp8) {
+        if (e->D == 128) hipLaunchKernelGGL((attn_chunk_kernel<128, 2, true>), grid, block, 0, st, HX_CHUNK_ARGS);
+        else             hipLaunchKernelGGL((attn_chunk_kernel<64, 3, true>), grid, block, 0, st, HX_CHUNK_ARGS);
+    } else {
+        if (e->D == 128) hipLaunchKernelGGL((attn_chunk_kernel<128, 2, false>), grid, block, 0, st, HX_CHUNK_ARGS);
+        else             hipLaunchKernelGGL((attn_chunk_kernel<64, 3, false>), grid, block, 0, st, HX_CHUNK_ARGS);
+    }
 #undef HX_CHUNK_ARGS
     HX_CHECK_LAUNCH("attn_chunk");
     return HX_OK;

@@ -212,8 +212,12 @@ int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, cons
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), e->cfg.n_kv_heads, e->G, scale_log2e,                              \
         (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
+    // Ring depth 6 for both head sizes.  At head size 64, depths 2, 4 and 8 gave wrong results whenever a run was
+    // longer than the ring (depths 3, 5, 6, 7 and 12 are right, as is the bf16 kernel at depth 4); reading the
+    // generated code did not show why, so the depth is fixed at a verified value and the tests run both head sizes
+    // with runs of 30+ tiles.
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
-    else             hipLaunchKernelGGL((attn_splitk_fp8_kernel<64, 8>), grid, block, 0, st, HX_ATTN8_ARGS);
+    else             hipLaunchKernelGGL((attn_splitk_fp8_kernel<64, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
 #undef HX_ATTN8_ARGS
     HX_CHECK_LAUNCH("attn_splitk_fp8");
     return HX_OK;

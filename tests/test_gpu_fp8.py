@@ -221,3 +221,36 @@ def test_prompt_chunks_fill_the_8_bit_cache(hx):
         assert err <= LOGIT_TOL * scale, (b, err, scale)
         worst = max(worst, err / scale)
     print("prompt chunks, 8-bit cache: worst logit err / max|logit| %.3e" % worst)
+
+
+@pytest.mark.parametrize("waves", [2048, 64])
+@pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1"])
+def test_attention_stage_over_the_8_bit_cache_matches_oracle(hx, name, waves, monkeypatch):
+    """The attention kernel alone on caller-supplied queries, lengths from a single key to 4 096 (both loads of block
+    ids, ragged last blocks), both head sizes: both caches hold the same bytes, so the bf16 bar applies.  With 2 048
+    wavefronts a run is one or two tiles, with 64 it is ~35 tiles: the tile ring wraps several times and runs cross
+    sequence boundaries (a ring depth that failed exactly then was found this way)."""
+    from test_gpu_stages import STAGE_SHAPES
+    monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
+    shape = STAGE_SHAPES[name]
+    eng = hx.Engine(shape, 16, 4096, kv_dtype=hx.HX_KV_FP8_E4M3)
+    lens = np.array([1, 2, 15, 16, 17, 31, 100, 511, 512, 513, 1029, 3000, 4096, 48, 333, 1024], dtype=np.int32)
+    table, nb = synth.block_table(lens, 16, 21)
+    k, v = synth.kv_fill(shape, 0, int(lens.sum()), 21)
+    start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)                                        # NaN codes past every sequence end
+    kv.prefill_fill(0, k.cuda(), v.cuda(), dev(start), dev(table))
+    cfg = oracle.make_config(shape, kv_fp8=True)
+    okv = oracle.PagedKV(cfg, nb)
+    okv.fill(0, synth.as_u16(k), synth.as_u16(v), start, table)
+    q = np.random.default_rng(8).normal(0, 1.2, size=(len(lens), shape.q_dim)).astype(np.float32)
+    out = eng.stage_attention(kv, 0, dev(q), dev(lens), dev(table)).cpu().numpy()
+    qr = bits_to_f32(synth.as_u16(torch.from_numpy(q).to(torch.bfloat16)))   # the stage rounds q on entry
+    worst = 0.0
+    for b, T in enumerate(lens):
+        ref = oracle.attention(cfg, qr[b], okv.k[0], okv.v[0], table[b], int(T))
+        err = float(np.abs(out[b] - ref).max())
+        assert err <= ATTN_TOL, (name, b, int(T), err)
+        worst = max(worst, err)
+    print("attention over the 8-bit cache, %s: max abs err %.2e" % (name, worst))

@@ -31,8 +31,8 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def build(hx, shape, seed, max_batch, max_seq_len):
-    eng = hx.Engine(shape, max_batch, max_seq_len)
+def build(hx, shape, seed, max_batch, max_seq_len, kv_dtype=0):
+    eng = hx.Engine(shape, max_batch, max_seq_len, kv_dtype=kv_dtype)
     for l in range(shape.n_layers):
         eng.pack_layer(l, synth.layer_weights(shape, l, seed))
     eng.pack_globals(synth.global_weights(shape, seed))
@@ -88,9 +88,14 @@ SHAPES = {
 }
 
 
+@pytest.mark.parametrize("cache", ["bf16", "fp8"])
 @pytest.mark.parametrize("name", sorted(SHAPES))
-def test_grouped_attention_equals_row_at_a_time_attention(hx, name, monkeypatch):
+def test_grouped_attention_equals_row_at_a_time_attention(hx, name, cache, monkeypatch):
+    """cache = fp8: the 8-bit cache variant on both paths.  There a last-bit difference in layer 0's output can move
+    a K or V of layer 1 to the neighbouring E4M3 value (1/16 of its magnitude), which a short sequence feels: layer 1
+    is then held to a mean difference of 1e-4 and a worst one of a format step on an O(1) value."""
     s = SHAPES[name]
+    kv_dtype = hx.HX_KV_FP8_E4M3 if cache == "fp8" else hx.HX_KV_BF16
     seed = 123
     # (keys already cached, rows in this call): long context crossing blocks, a fresh sequence, single rows, a run of
     # exactly 8, a long run from an unaligned position
@@ -108,7 +113,7 @@ def test_grouped_attention_equals_row_at_a_time_attention(hx, name, monkeypatch)
     caps, pools, logits = [], [], []
     for flag in ("0", "1"):
         monkeypatch.setenv("HX_CHUNK_ATTENTION", flag)
-        eng = build(hx, s, seed, 256, int(final.max()) + 1)
+        eng = build(hx, s, seed, 256, int(final.max()) + 1, kv_dtype)
         kv = hx.KVCache(eng, nb)
         kv.pool.fill_(0xFF)
         for l in range(s.n_layers):
@@ -132,9 +137,14 @@ def test_grouped_attention_equals_row_at_a_time_attention(hx, name, monkeypatch)
     scale = float(np.abs(rowwise[0]).max())
     d0 = float(np.abs(grouped[0] - rowwise[0]).max())
     d1 = float(np.abs(grouped[1] - rowwise[1]).max())
-    print("%s: layer-0 attention max |grouped - row-wise| %.2e (max |o| %.2f), layer 1 %.2e" % (name, d0, scale, d1))
+    m1 = float(np.abs(grouped[1] - rowwise[1]).mean())
+    print("%s %s: layer-0 attention max |grouped - row-wise| %.2e (max |o| %.2f), layer 1 max %.2e mean %.2e"
+          % (name, cache, d0, scale, d1, m1))
     assert d0 <= 2e-5 * max(scale, 1.0), (name, d0, scale)     # the same products, summed over different runs
-    assert d1 <= 1e-2, (name, d1)                              # after a layer of bf16 rounding points: the contract bar
+    if cache == "bf16":
+        assert d1 <= 1e-2, (name, d1)                          # after a layer of bf16 rounding points: the contract bar
+    else:
+        assert m1 <= 1e-4 and d1 <= 0.25, (name, m1, d1)
     ls = float(np.abs(logits[0]).max())
     assert float(np.abs(logits[1] - logits[0]).max()) <= LOGIT_TOL * ls
     # layer 0's K and V do not depend on attention: the two caches agree bit for bit there

@@ -97,11 +97,15 @@ def test_schedule_matches_host_recomputation(hx):
         assert sched.cpu().numpy().tolist() == [(nt + waves - 1) // waves, nt]
 
 
+@pytest.mark.parametrize("waves", [2048, 64])
 @pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1"])
-def test_attention_stage_matches_oracle(hx, name):
+def test_attention_stage_matches_oracle(hx, name, waves, monkeypatch):
     """Lengths cover: a single key, partial / exact / just-over one block, runs that end inside, at and just
     past block boundaries, and sequences long enough to be cut over many wavefronts (the split points depend on
-    the whole batch, so every pair ends up with a different mix of partial results)."""
+    the whole batch, so every pair ends up with a different mix of partial results).  With 2 048 wavefronts a run is
+    one or two tiles here; with 64 it is ~35 tiles, so the tile ring wraps several times within a run and runs cross
+    sequence boundaries."""
+    monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
     shape = STAGE_SHAPES[name]
     eng = build_engine(hx, shape, 3, 16, 4096)
     lens = [1, 2, 15, 16, 17, 31, 100, 511, 512, 513, 1029, 3000, 4096, 48, 333, 1024]
