@@ -248,6 +248,10 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
                     st.o[cb][2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_lo, st.o[cb][2 * q + 1], 0, 0, 0);
                 }
             }
+            if (FP8) {                                         // converted operands outlive the products that read them
+                hx_hold_operands(kop);
+                hx_hold_operands(vv);
+            }
             // the slot is free: request tile i + PF into it (or the query once the run is exhausted)
             const int nx = i + PF;
             const int32_t blk = (nx < 64) ? __builtin_amdgcn_readlane(blk_lo, nx & 63) : __builtin_amdgcn_readlane(blk_hi, nx & 63);

@@ -47,15 +47,19 @@ __device__ __forceinline__ void stream_tiles8(AttnState8<D> &st, const bf16x8_t 
             const int i = (rd - 1) * PF + s;                   // tile of this iteration; < 0 while the ring fills
             const int tok0 = t0 + i * 16 + qd * 4;             // this lane's 4 tokens
             // scores of 16 tokens x 16 query heads; operand step kk = dwords 2 (kk % 2), 2 (kk % 2) + 1 of load kk / 2
-            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            u32x4_t kop[D / 32];
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk) {
                 const u32x4_t raw = ring[s][kk >> 1];
                 const uint2 a = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.z : raw.x);
                 const uint2 b = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.w : raw.y);
-                const uint4 kop = make_uint4(a.x, a.y, b.x, b.y);
-                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop), qop[kk], sc, 0, 0, 0);
+                kop[kk] = u32x4_t{a.x, a.y, b.x, b.y};
             }
+            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk)
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]), qop[kk], sc, 0, 0, 0);
+            hx_hold_operands(kop);                             // converted operands outlive the products that read them
             float s4[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r >= t0 && tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
@@ -95,15 +99,22 @@ __device__ __forceinline__ void stream_tiles8(AttnState8<D> &st, const bf16x8_t 
             pl.y = hx_cvt_pk_bf16(p[2] - __uint_as_float(ph.y << 16), p[3] - __uint_as_float(ph.y & 0xffff0000u));
             const s16x4_t pop_hi = __builtin_bit_cast(s16x4_t, ph);
             const s16x4_t pop_lo = __builtin_bit_cast(s16x4_t, pl);
+            u32x4_t vop[D / 32];                               // x, y: rows d < 16 of the step; z, w: rows d >= 16
 #pragma unroll
             for (int q = 0; q < D / 32; ++q) {
-                const s16x4_t lo = __builtin_bit_cast(s16x4_t, hx_e4m3x4_to_bf16x4(vlo[q]));
-                const s16x4_t hi = __builtin_bit_cast(s16x4_t, hx_e4m3x4_to_bf16x4(vhi[q]));
+                const uint2 lo2 = hx_e4m3x4_to_bf16x4(vlo[q]), hi2 = hx_e4m3x4_to_bf16x4(vhi[q]);
+                vop[q] = u32x4_t{lo2.x, lo2.y, hi2.x, hi2.y};
+            }
+#pragma unroll
+            for (int q = 0; q < D / 32; ++q) {
+                const s16x4_t lo = __builtin_bit_cast(s16x4_t, make_uint2(vop[q].x, vop[q].y));
+                const s16x4_t hi = __builtin_bit_cast(s16x4_t, make_uint2(vop[q].z, vop[q].w));
                 st.o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(lo, pop_hi, st.o[2 * q], 0, 0, 0);
                 st.o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hi, pop_hi, st.o[2 * q + 1], 0, 0, 0);
                 st.o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(lo, pop_lo, st.o[2 * q], 0, 0, 0);
                 st.o[2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hi, pop_lo, st.o[2 * q + 1], 0, 0, 0);
             }
+            hx_hold_operands(vop);
             // the slot is free: request tile i + PF into it (or the query once the run is exhausted)
             const int nx = i + PF;
             const int32_t blk = (nx < 64) ? __builtin_amdgcn_readlane(blk_lo, nx & 63) : __builtin_amdgcn_readlane(blk_hi, nx & 63);
@@ -212,10 +223,6 @@ int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, cons
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), e->cfg.n_kv_heads, e->G, scale_log2e,                              \
         (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
-    // Ring depth 6 for both head sizes.  At head size 64, depths 2, 4 and 8 gave wrong results whenever a run was
-    // longer than the ring (depths 3, 5, 6, 7 and 12 are right, as is the bf16 kernel at depth 4); reading the
-    // generated code did not show why, so the depth is fixed at a verified value and the tests run both head sizes
-    // with runs of 30+ tiles.
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
     else             hipLaunchKernelGGL((attn_splitk_fp8_kernel<64, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
 #undef HX_ATTN8_ARGS

@@ -78,6 +78,19 @@ __device__ __forceinline__ uint2 hx_e4m3x4_to_bf16x4(uint32_t w) {
     const hx_bf16x2_t hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
     return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
 }
+// Registers holding operands that were converted for a matrix instruction die with that instruction, so the
+// compiler may hand them to the very next vector instruction -- and on this device a vector write that follows a
+// 16x16x32 matrix instruction within a few issue slots was seen to corrupt the A operand the matrix instruction was
+// still reading (deterministic wrong scores in the 8-bit attention kernel whenever the masking code of a ragged tile
+// reused those registers; the compiler's hazard handling leaves no gap there).  Operands that stay live -- the bf16
+// kernels multiply straight out of their load registers -- are not exposed.  This keeps the converted operands
+// live for eight more wait states.
+template <int N>
+__device__ __forceinline__ void hx_hold_operands(const unsigned int __attribute__((ext_vector_type(4))) (&op)[N]) {
+    if constexpr (N == 4) asm volatile("s_nop 7" : : "v"(op[0]), "v"(op[1]), "v"(op[2]), "v"(op[3]));
+    else if constexpr (N == 2) asm volatile("s_nop 7" : : "v"(op[0]), "v"(op[1]));
+    else static_assert(N == 2 || N == 4, "operand steps of head sizes 64 and 128");
+}
 
 // round-to-nearest-even on the upper half of the fp32 pattern (finite inputs)
 __device__ __forceinline__ uint16_t hx_f32_to_bf16(float f) {
