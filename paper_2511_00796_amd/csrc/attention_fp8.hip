@@ -48,17 +48,15 @@ __device__ __forceinline__ void stream_tiles8(AttnState8<D> &st, const bf16x8_t 
             const int tok0 = t0 + i * 16 + qd * 4;             // this lane's 4 tokens
             // scores of 16 tokens x 16 query heads; operand step kk = dwords 2 (kk % 2), 2 (kk % 2) + 1 of load kk / 2
             u32x4_t kop[D / 32];
+            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk) {
                 const u32x4_t raw = ring[s][kk >> 1];
                 const uint2 a = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.z : raw.x);
                 const uint2 b = hx_e4m3x4_to_bf16x4((kk & 1) ? raw.w : raw.y);
                 kop[kk] = u32x4_t{a.x, a.y, b.x, b.y};
-            }
-            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk)
                 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]), qop[kk], sc, 0, 0, 0);
+            }
             hx_hold_operands(kop);                             // converted operands outlive the products that read them
             float s4[4];
 #pragma unroll
@@ -104,9 +102,6 @@ __device__ __forceinline__ void stream_tiles8(AttnState8<D> &st, const bf16x8_t 
             for (int q = 0; q < D / 32; ++q) {
                 const uint2 lo2 = hx_e4m3x4_to_bf16x4(vlo[q]), hi2 = hx_e4m3x4_to_bf16x4(vhi[q]);
                 vop[q] = u32x4_t{lo2.x, lo2.y, hi2.x, hi2.y};
-            }
-#pragma unroll
-            for (int q = 0; q < D / 32; ++q) {
                 const s16x4_t lo = __builtin_bit_cast(s16x4_t, make_uint2(vop[q].x, vop[q].y));
                 const s16x4_t hi = __builtin_bit_cast(s16x4_t, make_uint2(vop[q].z, vop[q].w));
                 st.o[2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(lo, pop_hi, st.o[2 * q], 0, 0, 0);
