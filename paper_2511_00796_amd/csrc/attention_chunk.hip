@@ -197,12 +197,15 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
 #pragma unroll
             for (int cb = 0; cb < HX_CHUNK_CB; ++cb) {
                 if (cb >= n_cb) continue;                     // wave-uniform: column blocks no row of the group uses
+                u32x4_t qb[D / 32];                            // this column block's query operands, from LDS
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) qb[kk] = qs[(cb * (D / 32) + kk) * 64 + lane];
                 f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < D / 32; ++kk)
                     sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]),
-                                                                 __builtin_bit_cast(bf16x8_t, qs[(cb * (D / 32) + kk) * 64 + lane]),
-                                                                 sc, 0, 0, 0);
+                                                                 __builtin_bit_cast(bf16x8_t, qb[kk]), sc, 0, 0, 0);
+                hx_hold_operands(qb);                          // short-lived operands outlive the products that read them
                 float s4[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) s4[r] = sc[r] * scale_log2e;
