@@ -4,8 +4,9 @@
 // tile (K and V of 16 tokens of one KV head) holds 1-byte elements in the operand order of the bf16 tile with the bytes
 // of two operand steps side by side (hx_ktile8_index / hx_vtile8_index), so it is half as many 1-KiB loads.  Each
 // operand is converted to bf16 in registers right before its product -- exactly, every E4M3 value is a bf16 value --
-// and from there on the arithmetic is the bf16 kernel's.  The ring holds the raw bytes: twice as many tiles in flight
-// for the same registers and the same bytes outstanding.
+// and from there on the arithmetic is the bf16 kernel's.  The ring holds the raw bytes (4 tiles of 4 KiB in flight at
+// head size 128: with the converted operands held in registers past their products, a deeper ring costs more in
+// register pressure than it gains; measured 194 us per launch at depth 4, 207 at depth 6, 214 at depth 7).
 #include "hx_internal.h"
 
 #define HX_NEG_BIG (-1.0e30f)
@@ -218,7 +219,9 @@ int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, cons
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), e->cfg.n_kv_heads, e->G, scale_log2e,                              \
         (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
-    if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
+    // ring depths: 128: see the header; 64: depth 6 (depths 2 and 4 gave wrong results on long runs at this head size
+    // for a reason not found in the generated code; 3, 5, 6, 7, 8, 12 are right, and the tests cover long runs)
+    if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 4>), grid, block, 0, st, HX_ATTN8_ARGS);
     else             hipLaunchKernelGGL((attn_splitk_fp8_kernel<64, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
 #undef HX_ATTN8_ARGS
     HX_CHECK_LAUNCH("attn_splitk_fp8");
