@@ -1,0 +1,112 @@
+"""Generated code of the attention kernels whose matrix operands are short-lived registers (the 8-bit cache kernels
+convert K and V bytes into operand registers just before each product; the grouped prompt kernel reads its query
+operands back from LDS): no ordinary vector instruction may write a register within a few issue slots behind a
+16x16x32 matrix product that reads it.  On the hardware such a write, a handful of slots behind the product, has
+changed the product's result; the kernels hold their operands past the products with an empty asm statement, and
+this test checks on the compiler's assembly output that the hold is still effective -- a guard against scheduling
+changes in the kernels or the compiler, which a numerical test only catches at the run lengths it happens to use.
+
+Runs the device compiler only (-S, no GPU)."""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2511_00796_amd import build as hxbuild
+
+WINDOW = 6      # issue slots; the shipped kernels keep 7 or more, the failures seen on hardware had 4 or fewer
+GUARDED = ["attention_fp8.hip", "attention_chunk.hip"]
+
+
+def reg_set(tok):
+    tok = tok.strip().rstrip(",")
+    m = re.match(r"([va])\[(\d+):(\d+)\]$", tok)
+    if m:
+        return m.group(1), set(range(int(m.group(2)), int(m.group(3)) + 1))
+    m = re.match(r"([va])(\d+)$", tok)
+    if m:
+        return m.group(1), {int(m.group(2))}
+    return None, set()
+
+
+def instructions(text):
+    """(kernel, instruction) in program order; labels and directives dropped (the scan follows fall-through)."""
+    kernel, out = None, []
+    for line in text.splitlines():
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            kernel = m.group(1)
+            continue
+        t = line.split(";")[0].strip()
+        if not t or t.startswith(".") or t.endswith(":"):
+            continue
+        out.append((kernel, t))
+    return out
+
+
+def exposures(text, window):
+    """Ordinary vector writes (no accumulator moves, compares or lane reads) to a register that a 16x16x32 product
+    read as its first or second operand at most `window` issue slots earlier on the fall-through path."""
+    ins = instructions(text)
+    found = []
+    for i, (kernel, t) in enumerate(ins):
+        if not t.startswith("v_mfma") or "16x16x32" not in t:
+            continue
+        ops = t.split(None, 1)[1].split(",")
+        src = set()
+        for o in ops[1:3]:
+            f, r = reg_set(o)
+            if f == "v":
+                src |= r
+        dist = 0
+        for k2, t2 in ins[i + 1:i + 1 + 4 * window]:
+            op = t2.split()[0]
+            if op.startswith("s_branch") or op.startswith("s_endpgm") or op.startswith("s_setpc"):
+                break
+            dist += int(t2.split()[1]) + 1 if op.startswith("s_nop") else 1
+            if dist > window:
+                break
+            if not op.startswith("v_") or op.startswith(("v_mfma", "v_cmp", "v_readlane", "v_readfirstlane",
+                                                          "v_accvgpr")):
+                continue
+            f, r = reg_set(t2.split(None, 1)[1].split(",")[0])
+            if f == "v" and r & src:
+                found.append((kernel, dist, t, t2))
+    return found
+
+
+def test_the_scan_sees_a_planted_write_and_respects_the_window():
+    base = """
+_Z4demov:
+	v_mfma_f32_16x16x32_bf16 a[0:3], v[10:13], v[2:5], a[0:3]
+	s_add_u32 s0, s0, 1
+%s
+	v_add_u32_e32 v12, 1, v40
+	s_endpgm
+"""
+    near = exposures(base % "", 6)
+    assert len(near) == 1 and near[0][1] == 2 and "v12" in near[0][3]
+    assert exposures(base % "\ts_nop 3", 6) == [("_Z4demov", 6, near[0][2], near[0][3])]
+    assert exposures(base % "\ts_nop 4", 6) == []
+    # a write to another register, an accumulator move and a product of another shape are not reported
+    other = base.replace("v12, 1, v40", "v14, 1, v40")
+    assert exposures(other % "", 6) == []
+    assert exposures(base.replace("v_add_u32_e32 v12, 1, v40", "v_accvgpr_read_b32 v12, a5") % "", 6) == []
+    assert exposures(base.replace("16x16x32_bf16", "32x32x8_bf16") % "", 6) == []
+    # labels and conditional branches do not hide the fall-through path
+    through = base % "\ts_cbranch_vccnz .LBB0_3\n.LBB0_2:"
+    assert len(exposures(through, 6)) == 1 and exposures(through, 6)[0][1] == 3
+
+
+@pytest.mark.parametrize("source", GUARDED)
+def test_no_vector_write_close_behind_a_product_that_reads_the_register(source, tmp_path):
+    out = tmp_path / (source + ".s")
+    cmd = [hxbuild.HIPCC, *[f for f in hxbuild.FLAGS if f != "-fPIC"], "--cuda-device-only", "-S",
+           os.path.join(hxbuild.CSRC, source), "-o", str(out)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    text = out.read_text()
+    assert "v_mfma_f32_16x16x32_bf16" in text
+    found = exposures(text, WINDOW)
+    assert not found, "\n".join("%s: %d slots: %s <- %s" % (k[:60], d, a, b) for k, d, a, b in found[:10])
