@@ -15,8 +15,10 @@ import pytest
 
 from paper_2511_00796_amd import build as hxbuild
 
-WINDOW = 6      # issue slots; the shipped kernels keep 7 or more, the failures seen on hardware had 4 or fewer
-GUARDED = ["attention_fp8.hip", "attention_chunk.hip"]
+# (source, window in issue slots).  The failures seen on hardware had such a write 4 or fewer slots behind the
+# product.  The 8-bit and grouped kernels keep 7 or more; the bf16 decode kernel multiplies out of its load registers
+# and has one write 5 slots behind a product (head size 64), right at every run length the parity tests cover.
+GUARDED = [("attention_fp8.hip", 6), ("attention_chunk.hip", 6), ("attention.hip", 4)]
 
 
 def reg_set(tok):
@@ -99,8 +101,8 @@ _Z4demov:
     assert len(exposures(through, 6)) == 1 and exposures(through, 6)[0][1] == 3
 
 
-@pytest.mark.parametrize("source", GUARDED)
-def test_no_vector_write_close_behind_a_product_that_reads_the_register(source, tmp_path):
+@pytest.mark.parametrize("source,window", GUARDED)
+def test_no_vector_write_close_behind_a_product_that_reads_the_register(source, window, tmp_path):
     out = tmp_path / (source + ".s")
     cmd = [hxbuild.HIPCC, *[f for f in hxbuild.FLAGS if f != "-fPIC"], "--cuda-device-only", "-S",
            os.path.join(hxbuild.CSRC, source), "-o", str(out)]
@@ -108,5 +110,5 @@ def test_no_vector_write_close_behind_a_product_that_reads_the_register(source, 
     assert r.returncode == 0, r.stderr[-2000:]
     text = out.read_text()
     assert "v_mfma_f32_16x16x32_bf16" in text
-    found = exposures(text, WINDOW)
+    found = exposures(text, window)
     assert not found, "\n".join("%s: %d slots: %s <- %s" % (k[:60], d, a, b) for k, d, a, b in found[:10])
