@@ -354,6 +354,19 @@ def test_degenerate_batches_parity(hx, batch, lo, hi):
     assert res[2] == 1.0
 
 
+@pytest.mark.parametrize("waves", [2048, 64])
+def test_sequences_far_longer_than_the_benchmarks(hx, waves, monkeypatch):
+    """Two sequences of 150 000 to 200 000 keys (up to 12 501 blocks in a table row) on 1.5B-shaped layers (2 of
+    them).  With the default 2048 wavefronts a run is ~11 tiles; with 64 wavefronts a run is ~340 tiles of one
+    (sequence, head) pair, which takes the block ids in several loads of 128 and ends on a ragged one."""
+    monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
+    wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=2, lo=150000, hi=200000)
+    res, dw = run_sampled(hx, wl, 2, [0, 1], with_floor=True)
+    assert dw.engine.attention_waves() == waves
+    print("long sequences, %d wavefronts: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f" % ((waves,) + res))
+    assert res[2] == 1.0
+
+
 @pytest.mark.parametrize("name", ["1.5b-b64", "1.5b-b256-longtail", "7b-b128", "14b-b64"])
 def test_full_size_sampled_rows_parity(hx, name):
     """Configs 2-5 at full size, in the launch configuration the benchmark times: the oracle recomputes
