@@ -354,16 +354,19 @@ def test_degenerate_batches_parity(hx, batch, lo, hi):
     assert res[2] == 1.0
 
 
+@pytest.mark.parametrize("cache", ["bf16", "fp8"])
 @pytest.mark.parametrize("waves", [2048, 64])
-def test_sequences_far_longer_than_the_benchmarks(hx, waves, monkeypatch):
+def test_sequences_far_longer_than_the_benchmarks(hx, waves, cache, monkeypatch):
     """Two sequences of 150 000 to 200 000 keys (up to 12 501 blocks in a table row) on 1.5B-shaped layers (2 of
     them).  With the default 2048 wavefronts a run is ~11 tiles; with 64 wavefronts a run is ~340 tiles of one
-    (sequence, head) pair, which takes the block ids in several loads of 128 and ends on a ragged one."""
+    (sequence, head) pair, which takes the block ids in several loads of 128 and ends on a ragged one.  cache = fp8:
+    the 8-bit cache variant and its kernel, on both sides."""
     monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
     wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=2, lo=150000, hi=200000)
-    res, dw = run_sampled(hx, wl, 2, [0, 1], with_floor=True)
+    res, dw = run_sampled(hx, wl, 2, [0, 1], with_floor=True, kv_fp8=cache == "fp8")
     assert dw.engine.attention_waves() == waves
-    print("long sequences, %d wavefronts: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f" % ((waves,) + res))
+    print("long sequences, %s cache, %d wavefronts: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f"
+          % ((cache, waves) + res))
     assert res[2] == 1.0
 
 
