@@ -224,7 +224,7 @@ def test_prompt_chunks_fill_the_8_bit_cache(hx):
 
 
 @pytest.mark.parametrize("waves", [2048, 64])
-@pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1"])
+@pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1", "d64_g16", "d128_g12"])
 def test_attention_stage_over_the_8_bit_cache_matches_oracle(hx, name, waves, monkeypatch):
     """The attention kernel alone on caller-supplied queries, lengths from a single key to 4 096 (both loads of block
     ids, ragged last blocks), both head sizes: both caches hold the same bytes, so the bf16 bar applies.  With 2 048

@@ -79,6 +79,48 @@ def test_long_prompt_in_256_row_chunks_matches_dense_causal_recomputation(hx):
     print("2300-token prompt in 256-row chunks: worst logit err / max|logit| %.3e" % worst)
 
 
+@pytest.mark.parametrize("name,heads,kv_heads,head_dim", [("g16_d64", 16, 1, 64), ("g12_d128", 12, 1, 128),
+                                                          ("g9_d64", 18, 2, 64)])
+def test_more_than_8_query_heads_per_kv_head(hx, name, heads, kv_heads, head_dim):
+    """Above 8 query heads per KV head a group of 8 rows no longer fits the 64 columns of the grouped kernel, so prompt
+    rows take the decode step's attention; 16 is the most the library accepts.  Three prompts through one prefill_chunk
+    call each chunk, then one decode step, against the oracle's dense causal recomputation."""
+    s = synth.ModelShape("prefill-" + name, 2, 256, heads, kv_heads, head_dim, 688, 1024)
+    seed = 17
+    ow, g, layers = host_model(s, seed)
+    cfg = oracle.make_config(s)
+    rng = np.random.default_rng(seed)
+    ctx = np.array([70, 33, 41], dtype=np.int32)
+    prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
+    table, nb = synth.block_table(ctx + 1, s.block_size, seed)
+    eng = build(hx, s, seed, 64, int(ctx.max()) + 1)
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    rows = [(b, p) for b in range(len(ctx)) for p in range(int(ctx[b]) - 1)]
+    for at in range(0, len(rows), 64):
+        chunk = rows[at:at + 64]
+        bs = np.array([b for b, _ in chunk])
+        ps = np.array([p for _, p in chunk], dtype=np.int32)
+        toks = np.array([prompts[b][p] for b, p in chunk], dtype=np.int32)
+        eng.prefill_chunk(kv, dev(toks), dev(ps), dev(ps + 1), dev(table[bs]))
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[b][-1] for b in range(len(ctx))], dtype=np.int32)
+    logits = torch.empty(len(ctx), s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(len(ctx), dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    worst = 0.0
+    for b in range(len(ctx)):
+        ref = oracle.full_causal(cfg, ow, prompts[b])[0][-1]
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(gl[b] - ref).max())
+        assert err <= LOGIT_TOL * scale, (name, b, err, scale)
+        assert int(nxt[b]) == int(np.argmax(ref)) or np.sort(ref)[-1] - np.sort(ref)[-2] < 2 * err
+        worst = max(worst, err / scale)
+    print("%s: worst logit err / max|logit| %.3e" % (name, worst))
+
+
 SHAPES = {
     "g7_d128": synth.ModelShape("chunk-g7", 3, 512, 14, 2, 128, 1376, 2048),
     "g5_d128": synth.ModelShape("chunk-g5", 3, 512, 10, 2, 128, 1376, 2048),

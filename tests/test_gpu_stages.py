@@ -16,6 +16,8 @@ STAGE_SHAPES = {
     "d128_g7": synth.ModelShape("stage-d128-g7", 1, 512, 14, 2, 128, 1376, 2048),
     "d64_g2": synth.ModelShape("stage-d64-g2", 1, 256, 4, 2, 64, 688, 1024),
     "d128_g1": synth.ModelShape("stage-d128-g1", 1, 256, 2, 2, 128, 336, 1000),
+    "d64_g16": synth.ModelShape("stage-d64-g16", 1, 256, 16, 1, 64, 688, 1024),      # the most query heads per KV head
+    "d128_g12": synth.ModelShape("stage-d128-g12", 1, 256, 12, 1, 128, 688, 1024),
 }
 
 
@@ -98,7 +100,7 @@ def test_schedule_matches_host_recomputation(hx):
 
 
 @pytest.mark.parametrize("waves", [2048, 64])
-@pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1"])
+@pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1", "d64_g16", "d128_g12"])
 def test_attention_stage_matches_oracle(hx, name, waves, monkeypatch):
     """Lengths cover: a single key, partial / exact / just-over one block, runs that end inside, at and just
     past block boundaries, and sequences long enough to be cut over many wavefronts (the split points depend on
