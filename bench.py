@@ -194,11 +194,28 @@ def main():
         run()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        # the kernel a call spends most time in: the gate|up product (HIP events around it, 8 calls)
+        eng.profile_enable(["gemm_gate_up"])
+        for c in range(8):
+            pos = off_of_row + (c % (P // per_seq)) * per_seq
+            eng.prefill_chunk(kvc, toks, pos, pos + 1, table_rows[0])
+        torch.cuda.synchronize()
+        gu_ms, gu_n = eng.profile_read("gemm_gate_up")
+        eng.profile_enable([])
+        gu_avg_ms = gu_ms / max(gu_n, 1)
+        gu_flops = 2.0 * R * s.hidden * 2 * s.intermediate
+        call_flops = 2.0 * R * (s.weight_elements() - s.hidden * s.vocab)      # products of a call (no LM head)
         print(json.dumps({"metric": "prompt tokens/s through prefill_chunk (rows = prompt tokens)",
                           "value": R * calls / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
                           "rows_per_call": R, "ms_per_call": dt / calls * 1e3,
                           "config": {"workload": "%s-prefill" % s.name, "prompts": B, "prompt_len": P, "rows_per_sequence_per_call": per_seq}, "data": "synthetic",
-                          "dtype": "bf16"}))
+                          "dtype": "bf16",
+                          "product_flops_over_call_time_TFLOPs": call_flops / (dt / calls) / 1e12,
+                          "roofline": {"kernel": "gemm_stream_kernel (gate|up product, 256 rows)", "bound": "mfma",
+                                       "achieved": gu_flops / (gu_avg_ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                                       "frac": gu_flops / (gu_avg_ms * 1e-3) / 1e12 / 2500.0, "traffic": None,
+                                       "launches_timed": int(gu_n), "avg_launch_ms": gu_avg_ms,
+                                       "algorithmic_flops_per_launch": gu_flops}}))
         return
 
     t_build = time.perf_counter()
