@@ -99,14 +99,14 @@ def test_schedule_matches_host_recomputation(hx):
         assert sched.cpu().numpy().tolist() == [(nt + waves - 1) // waves, nt]
 
 
-@pytest.mark.parametrize("waves", [2048, 64])
+@pytest.mark.parametrize("waves", [2048, 64, 16384])
 @pytest.mark.parametrize("name", ["d128_g6", "d128_g7", "d64_g2", "d128_g1", "d64_g16", "d128_g12"])
 def test_attention_stage_matches_oracle(hx, name, waves, monkeypatch):
     """Lengths cover: a single key, partial / exact / just-over one block, runs that end inside, at and just
     past block boundaries, and sequences long enough to be cut over many wavefronts (the split points depend on
     the whole batch, so every pair ends up with a different mix of partial results).  With 2 048 wavefronts a run is
     one or two tiles here; with 64 it is ~35 tiles, so the tile ring wraps several times within a run and runs cross
-    sequence boundaries."""
+    sequence boundaries; 16 384 is the most the library accepts (every run a single tile, most wavefronts idle)."""
     monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
     shape = STAGE_SHAPES[name]
     eng = build_engine(hx, shape, 3, 16, 4096)
