@@ -213,8 +213,9 @@ int decode_step_top_p(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t
    before any row attends, so a row sees the rows before it); chunks of a sequence are submitted in position order.
    The last prompt token is then given to decode_step / decode_step_sample, which yields the first generated token.
    Consecutive rows that continue one another (seq_lens one more, the same table row) are attended in groups of up
-   to 8 that share one read of the cache, so a call should hold long runs of one sequence rather than one row of
-   many; any row order is correct.  Arguments, ownership and errors as decode_step. */
+   to 8 that share one read of the cache (models with at most 8 query heads per KV head; with more, every row reads
+   the cache on its own), so a call should hold long runs of one sequence rather than one row of many; any row order
+   is correct.  Arguments, ownership and errors as decode_step. */
 int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
 
