@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--prefill", type=int, default=0, metavar="P",
                     help="instead of decode steps, time prompt processing: 128 prompts of P tokens through prefill_chunk, "
                          "256 token rows per call (reported as prompt tokens/s)")
+    ap.add_argument("--prefill-streams", type=int, default=1, choices=[1, 2, 4], metavar="S",
+                    help="with --prefill: S engines over one copy of the packed weights, each with its own workspace, "
+                         "cache and stream, processing different prompts concurrently")
     ap.add_argument("--prefill-rows-per-seq", type=int, default=256, metavar="N",
                     help="with --prefill: consecutive positions of one prompt per call (256 = one prompt per call, "
                          "2 = all 128 prompts in every call)")
@@ -172,6 +175,14 @@ def main():
         table, nb = synth.block_table(lens, s.block_size, wl.seed)
         kvc = binding.KVCache(eng, nb)
         kvc.pool.zero_()
+        n_streams = args.prefill_streams
+        # further engines share the packed weights; each has its own workspace, cache and stream
+        lanes = [(eng, kvc, torch.cuda.current_stream())]
+        for _ in range(1, n_streams):
+            e2 = binding.Engine(s, R, P + 1, weights=eng.weights)
+            k2 = binding.KVCache(e2, nb)
+            k2.pool.zero_()
+            lanes.append((e2, k2, torch.cuda.Stream()))
         per_seq = args.prefill_rows_per_seq                  # consecutive positions of each sequence per call
         assert R % per_seq == 0 and P % per_seq == 0 and B % (R // per_seq) == 0
         seqs_per_call = R // per_seq
@@ -181,12 +192,18 @@ def main():
         table_rows = [table_d[seq_of_row + g * seqs_per_call].contiguous() for g in range(B // seqs_per_call)]
         toks = torch.randint(0, s.vocab, (R,), dtype=torch.int32, device="cuda")
         calls = (B // seqs_per_call) * (P // per_seq)
+        assert (B // seqs_per_call) % n_streams == 0
+
+        pos_of_chunk = [off_of_row + c * per_seq for c in range(P // per_seq)]
+        len_of_chunk = [p + 1 for p in pos_of_chunk]
+        torch.cuda.synchronize()                              # the arguments exist before any stream reads them
 
         def run():
-            for g in range(B // seqs_per_call):              # a set of sequences at a time, each from position 0 to P
+            for g in range(0, B // seqs_per_call, n_streams):   # a set of sequences at a time, each from position 0 to P
                 for c in range(P // per_seq):
-                    pos = off_of_row + c * per_seq
-                    eng.prefill_chunk(kvc, toks, pos, pos + 1, table_rows[g])
+                    for i, (e_i, kv_i, st_i) in enumerate(lanes):
+                        with torch.cuda.stream(st_i):
+                            e_i.prefill_chunk(kv_i, toks, pos_of_chunk[c], len_of_chunk[c], table_rows[g + i])
 
         run()
         torch.cuda.synchronize()
@@ -197,8 +214,8 @@ def main():
         # the kernel a call spends most time in: the gate|up product (HIP events around it, 8 calls)
         eng.profile_enable(["gemm_gate_up"])
         for c in range(8):
-            pos = off_of_row + (c % (P // per_seq)) * per_seq
-            eng.prefill_chunk(kvc, toks, pos, pos + 1, table_rows[0])
+            cc = c % (P // per_seq)
+            eng.prefill_chunk(kvc, toks, pos_of_chunk[cc], len_of_chunk[cc], table_rows[0])
         torch.cuda.synchronize()
         gu_ms, gu_n = eng.profile_read("gemm_gate_up")
         eng.profile_enable([])
@@ -208,7 +225,8 @@ def main():
         print(json.dumps({"metric": "prompt tokens/s through prefill_chunk (rows = prompt tokens)",
                           "value": R * calls / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
                           "rows_per_call": R, "ms_per_call": dt / calls * 1e3,
-                          "config": {"workload": "%s-prefill" % s.name, "prompts": B, "prompt_len": P, "rows_per_sequence_per_call": per_seq}, "data": "synthetic",
+                          "config": {"workload": "%s-prefill" % s.name, "prompts": B, "prompt_len": P, "rows_per_sequence_per_call": per_seq,
+                                     "streams": n_streams}, "data": "synthetic",
                           "dtype": "bf16",
                           "product_flops_over_call_time_TFLOPs": call_flops / (dt / calls) / 1e12,
                           "roofline": {"kernel": "gemm_stream_kernel (gate|up product, 256 rows)", "bound": "mfma",

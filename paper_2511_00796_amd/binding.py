@@ -143,11 +143,17 @@ def kv_bytes(cfg: ModelConfig, num_blocks: int) -> int:
 class Engine:
     """hx_engine plus the torch-owned device buffers it wraps."""
 
-    def __init__(self, shape, max_batch: int, max_seq_len: int, device="cuda:0", kv_dtype: int = HX_KV_BF16):
+    def __init__(self, shape, max_batch: int, max_seq_len: int, device="cuda:0", kv_dtype: int = HX_KV_BF16,
+                 weights: Optional[torch.Tensor] = None):
+        """weights: the packed-weight buffer of another engine of the same shape, to share it (each engine has its
+        own workspace, so two engines may run on two streams over one copy of the weights); None allocates one."""
         self.shape = shape
         self.cfg = make_config(shape, max_batch, max_seq_len, kv_dtype)
         self.device = torch.device(device)
-        self.weights = torch.empty(weights_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        if weights is None:
+            weights = torch.empty(weights_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        assert weights.dtype == torch.uint8 and weights.is_cuda and weights.is_contiguous()
+        self.weights = weights
         self.workspace = torch.empty(workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         h = C.c_void_p()
         _check(load().hx_engine_create(C.byref(self.cfg), _ptr(self.weights), self.weights.numel(),

@@ -214,3 +214,48 @@ def test_device_side_inputs_are_validated_without_running_the_step(hx):
         check(tab=tab)
     tab = table.copy(); tab[0, 3] = -7                        # past ceil(seq_len / 16) entries of row 0: ignored
     check(tab=tab)
+
+
+def test_two_engines_over_one_copy_of_the_weights_on_two_streams(hx):
+    """A second engine wraps the first one's packed weights with a workspace of its own; the two process different
+    prompts concurrently on two streams.  Each must leave exactly the cache, and produce exactly the logits, that
+    a single engine produces for the same calls alone: the step keeps no state outside its workspace and cache."""
+    a = engine_with(hx, 21, max_batch=64, max_seq_len=400)
+    b = hx.Engine(SHAPE, 64, 400, weights=a.weights)
+    rng = np.random.default_rng(5)
+    n_tok = [300, 260]
+    prompts = [rng.integers(0, SHAPE.vocab, size=n).astype(np.int32) for n in n_tok]
+    tables, pools = [], []
+    for n in n_tok:
+        t, nb = synth.block_table(np.array([n + 1]), 16, 40 + n)
+        tables.append((t, nb))
+
+    def process(eng, i, stream):
+        t, nb = tables[i]
+        kv = hx.KVCache(eng, nb)
+        with torch.cuda.stream(stream):
+            kv.pool.zero_()
+            for at in range(0, n_tok[i] - 1, 64):
+                ps = np.arange(at, min(at + 64, n_tok[i] - 1), dtype=np.int32)
+                eng.prefill_chunk(kv, dev(prompts[i][ps]), dev(ps), dev(ps + 1), dev(np.repeat(t, len(ps), axis=0)))
+            logits = torch.empty(1, SHAPE.vocab, dtype=torch.float32, device="cuda")
+            nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+            pos = np.array([n_tok[i] - 1], dtype=np.int32)
+            eng.decode_step(kv, dev(prompts[i][-1:]), dev(pos), dev(pos + 1), dev(t), logits, nxt)
+        return kv, logits, nxt
+
+    main = torch.cuda.current_stream()
+    alone = []
+    for i in range(2):                                   # one engine, one stream, one prompt after the other
+        kv, logits, nxt = process(a, i, main)
+        torch.cuda.synchronize()
+        alone.append((kv.pool.clone(), logits.clone(), nxt.clone()))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    together = [process(a, 0, s1), process(b, 1, s2)]    # both in flight at once
+    torch.cuda.synchronize()
+    for i in range(2):
+        kv, logits, nxt = together[i]
+        assert torch.equal(kv.pool, alone[i][0]), i
+        assert torch.equal(logits, alone[i][1]) and torch.equal(nxt, alone[i][2]), i
+    assert torch.isfinite(together[0][1]).all() and torch.isfinite(together[1][1]).all()
