@@ -111,7 +111,9 @@ int hx_kv_bytes(const hx_model_config *cfg, int64_t num_blocks, size_t *out);
 
 /* Wraps caller-owned DEVICE buffers (256-byte aligned, at least the sizes above).  No device work
    is done.  The buffers must outlive the engine.  *out receives a handle released with
-   hx_engine_destroy (which frees host state only). */
+   hx_engine_destroy (which frees host state only).  Several engines of one configuration may wrap the same weights
+   buffer, each with a workspace of its own: their calls may then run concurrently on different streams (only
+   hx_weights_pack writes the weights; order it against every engine that reads them). */
 int hx_engine_create(const hx_model_config *cfg, void *weights_dev, size_t weights_bytes,
                      void *workspace_dev, size_t workspace_bytes, hx_engine **out);
 int hx_engine_destroy(hx_engine *engine);
@@ -213,9 +215,9 @@ int decode_step_top_p(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t
    before any row attends, so a row sees the rows before it); chunks of a sequence are submitted in position order.
    The last prompt token is then given to decode_step / decode_step_sample, which yields the first generated token.
    Consecutive rows that continue one another (seq_lens one more, the same table row) are attended in groups of up
-   to 8 that share one read of the cache (models with at most 8 query heads per KV head; with more, every row reads
-   the cache on its own), so a call should hold long runs of one sequence rather than one row of many; any row order
-   is correct.  Arguments, ownership and errors as decode_step. */
+   to 8 that share one read of the cache (8 rows with at most 8 query heads per KV head, down to 4 rows with 16), so
+   a call should hold long runs of one sequence rather than one row of many; any row order is correct.  Arguments,
+   ownership and errors as decode_step. */
 int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
 

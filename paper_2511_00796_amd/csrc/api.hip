@@ -154,7 +154,8 @@ static int init_engine_shape(hx_engine *e, const hx_model_config *cfg) {
     e->attn_waves = attention_waves();
     // HX_CHUNK_ATTENTION=0: prompt rows go through the decode step's attention, one K/V stream per row (comparison)
     const char *ca = getenv("HX_CHUNK_ATTENTION");
-    e->chunk_attention = e->G <= HX_CHUNK_ROWS && !(ca && atoi(ca) == 0);
+    e->chunk_attention = !(ca && atoi(ca) == 0);
+    e->chunk_rows = 64 / e->G < HX_CHUNK_ROWS ? 64 / e->G : HX_CHUNK_ROWS;     // G <= 16: at least 4 rows
     return HX_OK;
 }
 

@@ -1,9 +1,10 @@
 // Attention for prompt rows (prefill_chunk): consecutive rows of one sequence share one K/V stream.
 //
 // A row of a prompt chunk is one token; row r of a sequence attends the keys [0, T_r), T_r = T_{r-1} + 1.  The decode
-// kernel would stream the whole prefix once per row.  Here up to HX_CHUNK_ROWS consecutive rows of one sequence form a
-// GROUP whose (row, query head) pairs are the columns of the score product -- 8 rows x G <= 8 heads = 64 columns = 4
-// column blocks of 16 -- so a K/V tile is loaded once per group and multiplied four times:
+// kernel would stream the whole prefix once per row.  Here up to min(HX_CHUNK_ROWS, 64 / G) consecutive rows of one
+// sequence form a GROUP whose (row, query head) pairs are the columns of the score product -- at most 64 columns = 4
+// column blocks of 16 (8 rows for G <= 8, 4 rows for G = 16) -- so a K/V tile is loaded once per group and multiplied
+// up to four times:
 //     S^T[token, (row, g)] = K_tile . q[row, g]          4 x v_mfma_f32_16x16x32_bf16 per column block
 //     O^T[d, (row, g)]    += V_tile^T . P^T               as in the decode kernel, per column block
 // The causal mask is per column: keys >= T_row are dropped (only the last tiles of a group differ between its rows).
@@ -52,7 +53,7 @@ __device__ __forceinline__ void scan_sum_256(int32_t *scan, int r) {     // incl
 // One workgroup of 256 threads (thread = row, later thread = group).  Writes the decode schedule's arrays with groups
 // in place of sequences -- pre[g] = blocks of the groups before g, lens[g] = keys of the group's last row, sched =
 // {tiles per wavefront, tiles} -- plus ginfo[g] = first row | rows << 16 and rgrp[r] = group | index in group << 16.
-__global__ __launch_bounds__(256) void chunk_setup_kernel(int n_rows, int n_kv, int n_waves,
+__global__ __launch_bounds__(256) void chunk_setup_kernel(int n_rows, int n_kv, int n_waves, int group_rows,
                                                           const int32_t *__restrict__ seq_lens,
                                                           const int32_t *__restrict__ cont, int32_t *__restrict__ pre,
                                                           int32_t *__restrict__ lens, int32_t *__restrict__ sched,
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(256) void chunk_setup_kernel(int n_rows, int n_kv, 
         scan[r] = max(scan[r], v);
         __syncthreads();
     }
-    const int local = (r - scan[r]) % HX_CHUNK_ROWS;          // index of r in its group
+    const int local = (r - scan[r]) % group_rows;             // index of r in its group
     const int gstart = (valid && local == 0) ? 1 : 0;
     __syncthreads();
     scan[r] = gstart;
@@ -446,7 +447,7 @@ int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_len
     int32_t *cont = (int32_t *)(ws + e->map.chunk_cont);
     hipLaunchKernelGGL(chunk_rows_kernel, dim3(n_rows), dim3(64), 0, st, seq_lens, table, max_blocks, cont);
     HX_CHECK_LAUNCH("chunk_rows");
-    hipLaunchKernelGGL(chunk_setup_kernel, dim3(1), dim3(256), 0, st, n_rows, e->cfg.n_kv_heads, e->attn_waves, seq_lens,
+    hipLaunchKernelGGL(chunk_setup_kernel, dim3(1), dim3(256), 0, st, n_rows, e->cfg.n_kv_heads, e->attn_waves, e->chunk_rows, seq_lens,
                        (const int32_t *)cont, (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
                        (int32_t *)(ws + e->map.sched), (int32_t *)(ws + e->map.chunk_ginfo),
                        (int32_t *)(ws + e->map.chunk_rgrp));

@@ -40,7 +40,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define HX_BLOCK_TOKENS 16
 #define HX_MAX_HIDDEN 8192
 #define HX_PREFIX_LEN 320    // entries of the per-step block prefix (max_batch 256 + 1, padded to 5 x 64)
-#define HX_CHUNK_ROWS 8      // consecutive prompt rows of one sequence that share a K/V stream (8 x G <= 64 columns)
+#define HX_CHUNK_ROWS 8      // most consecutive prompt rows of one sequence that share a K/V stream (rows x G <= 64 columns)
 #define HX_MAX_SPLITS 9       // K-splits of a product whose partials are summed by its consumer kernel
 
 // ---- error reporting (api.hip) -------------------------------------------------------------------
@@ -182,7 +182,8 @@ struct hx_engine {
     int G, D, q_dim, kv_dim, qkv_dim;
     int m_groups_max;       // ceil(max_batch / 32)
     int attn_waves;         // wavefronts of the attention kernel (8 per compute unit)
-    bool chunk_attention;     // prompt rows of one sequence share a K/V stream (G <= 8; HX_CHUNK_ATTENTION=0 disables)
+    bool chunk_attention;     // prompt rows of one sequence share a K/V stream (HX_CHUNK_ATTENTION=0 disables)
+    int chunk_rows;           // rows per group: min(HX_CHUNK_ROWS, 64 / G)
     char *weights;          // device
     char *ws;               // device
     size_t weights_bytes, ws_bytes;

@@ -82,9 +82,9 @@ def test_long_prompt_in_256_row_chunks_matches_dense_causal_recomputation(hx):
 @pytest.mark.parametrize("name,heads,kv_heads,head_dim", [("g16_d64", 16, 1, 64), ("g12_d128", 12, 1, 128),
                                                           ("g9_d64", 18, 2, 64)])
 def test_more_than_8_query_heads_per_kv_head(hx, name, heads, kv_heads, head_dim):
-    """Above 8 query heads per KV head a group of 8 rows no longer fits the 64 columns of the grouped kernel, so prompt
-    rows take the decode step's attention; 16 is the most the library accepts.  Three prompts through one prefill_chunk
-    call each chunk, then one decode step, against the oracle's dense causal recomputation."""
+    """Above 8 query heads per KV head a group holds fewer than 8 rows (64 columns / heads per KV head: 7 rows at 9,
+    5 at 12, 4 at 16, the most the library accepts).  Three prompts through prefill_chunk in 64-row chunks, then one
+    decode step, against the oracle's dense causal recomputation."""
     s = synth.ModelShape("prefill-" + name, 2, 256, heads, kv_heads, head_dim, 688, 1024)
     seed = 17
     ow, g, layers = host_model(s, seed)
@@ -122,6 +122,8 @@ def test_more_than_8_query_heads_per_kv_head(hx, name, heads, kv_heads, head_dim
 
 
 SHAPES = {
+    "g12_d128": synth.ModelShape("chunk-g12", 3, 512, 12, 1, 128, 1376, 2048),    # groups of 5 rows
+    "g16_d64": synth.ModelShape("chunk-g16", 3, 512, 16, 1, 64, 1376, 2048),      # groups of 4 rows
     "g7_d128": synth.ModelShape("chunk-g7", 3, 512, 14, 2, 128, 1376, 2048),
     "g5_d128": synth.ModelShape("chunk-g5", 3, 512, 10, 2, 128, 1376, 2048),
     "g8_d128": synth.ModelShape("chunk-g8", 3, 512, 8, 1, 128, 1376, 2048),
