@@ -286,7 +286,9 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
-    eng.profile_enable(["attention"])          # HIP events around the dominant kernel only
+    # HIP events around the dominant kernel only, and around every 4th of its launches (layers 0, 4, 8, ...: the same
+    # K/V lengths in every layer): a pair of events costs the stream ~5 us, 0.15 ms per step if all 28 were bracketed
+    eng.profile_enable(["attention"], every=4)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
@@ -294,6 +296,15 @@ def main():
     dt = time.perf_counter() - t0
     attn_ms, attn_n = eng.profile_read("attention")
     eng.profile_enable([])
+
+    # spread of single steps: a second pass with a pair of events per step (outside the timed region)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        one_step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch / (dt / args.steps)
@@ -320,6 +331,7 @@ def main():
                      "traffic_unit": "bytes per launch",
                      "launches_timed": int(attn_n), "avg_launch_ms": attn_avg_ms,
                      "algorithmic_bytes_per_launch": kv_bytes_per_launch},
+        "step_spread_ms": {"min": per_step[0], "median": per_step[len(per_step) // 2], "max": per_step[-1]},
         "setup_s": t_build,
     }
 

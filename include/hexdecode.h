@@ -317,6 +317,10 @@ typedef enum {
    0 switches timing off.  Bracketing adds a few microseconds per launch, so a throughput measurement
    should time at most the one class it reports. */
 int hx_profile_enable(hx_engine *engine, uint32_t class_mask);
+/* Brackets only every n-th launch of a selected class (counted from the last hx_profile_enable; default 1 = every
+   launch): a pair of events costs the stream about 5 us, which 28 bracketed launches per step would add to a
+   throughput measurement.  HX_E_RANGE for n < 1. */
+int hx_profile_sample_every(hx_engine *engine, int32_t n);
 /* Waits for the recorded events, adds up the elapsed time of class `kernel_class` since the last read,
    releases those events.  HOST out-pointers. */
 int hx_profile_read(hx_engine *engine, int kernel_class, double *total_ms_out, int64_t *launches_out);

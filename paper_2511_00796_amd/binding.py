@@ -23,7 +23,7 @@ EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_byt
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
            "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
-           "hx_profile_enable", "hx_profile_read"]
+           "hx_profile_enable", "hx_profile_sample_every", "hx_profile_read"]
 
 KERNEL_CLASSES = ["attention", "combine", "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm", "norm",
                   "rope_append", "setup"]
@@ -88,6 +88,7 @@ def load():
         "hx_stage_linear": [vp, C.c_int, C.c_int, i32, vp, vp, vp, vp],
         "hx_stage_lm_head_top_p": [vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "hx_profile_enable": [vp, C.c_uint32],
+        "hx_profile_sample_every": [vp, C.c_int32],
         "hx_profile_read": [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     }
     for name, args in sig.items():
@@ -227,7 +228,9 @@ class Engine:
         _check(load().hx_set_attn_capture(self.handle, _ptr(buf)))
 
     # -- per-kernel timing
-    def profile_enable(self, classes) -> None:
+    def profile_enable(self, classes, every: int = 1) -> None:
+        """every: bracket only every n-th launch of the selected classes."""
+        _check(load().hx_profile_sample_every(self.handle, every))
         mask = 0
         for c in classes:
             mask |= 1 << (KERNEL_CLASSES.index(c) if isinstance(c, str) else int(c))

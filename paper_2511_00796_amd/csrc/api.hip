@@ -219,6 +219,7 @@ extern "C" int hx_engine_create(const hx_model_config *cfg, void *weights_dev, s
     e->weights_bytes = weights_bytes;
     e->ws_bytes = workspace_bytes;
     e->profile_mask = 0;
+    e->profile_stride = 1;
     e->profile_events = new (std::nothrow) std::vector<std::pair<hipEvent_t, hipEvent_t>>[HX_K_COUNT];
     *out = e;
     return HX_OK;
@@ -342,7 +343,7 @@ extern "C" int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_d
 struct timed_launch {   // brackets one launch with two events when its class is selected
     hx_engine *e; int k; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
     timed_launch(hx_engine *e_, int k_, hipStream_t st_) : e(e_), k(k_), st(st_) {
-        if (e->profile_events && (e->profile_mask >> k) & 1u) {
+        if (e->profile_events && (e->profile_mask >> k) & 1u && e->profile_seen[k]++ % e->profile_stride == 0) {
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
             (void)hipEventRecord(a, st);
         }
@@ -357,6 +358,14 @@ extern "C" int hx_profile_enable(hx_engine *e, uint32_t class_mask) {
     if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
     if (class_mask >> HX_K_COUNT) return hx_fail(HX_E_RANGE, "class_mask has bits beyond HX_K_COUNT");
     e->profile_mask = class_mask;
+    for (int k = 0; k < HX_K_COUNT; ++k) e->profile_seen[k] = 0;
+    return HX_OK;
+}
+
+extern "C" int hx_profile_sample_every(hx_engine *e, int32_t n) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (n < 1) return hx_fail(HX_E_RANGE, "sampling stride %d must be at least 1", n);
+    e->profile_stride = n;
     return HX_OK;
 }
 

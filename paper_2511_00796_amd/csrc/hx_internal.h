@@ -193,6 +193,8 @@ struct hx_engine {
     hx_ws_map map;
     float *attn_capture;    // device or NULL
     uint32_t profile_mask;  // kernel classes bracketed by events
+    int profile_stride;     // every n-th launch of a selected class is bracketed (1: every launch)
+    int64_t profile_seen[HX_K_COUNT];   // launches of each class since hx_profile_enable
     std::vector<std::pair<hipEvent_t, hipEvent_t>> *profile_events;   // [HX_K_COUNT], host
 };
 

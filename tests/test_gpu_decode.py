@@ -247,6 +247,26 @@ def test_decode_step_is_deterministic_and_tokens_are_argmax_of_logits(hx):
     dw.step(with_logits=False)
     torch.cuda.synchronize()
     assert torch.equal(t1, dw.next_tokens)
+    # the timing hooks bracket what they are asked to and leave the results alone
+    eng = dw.engine
+    eng.profile_enable(["attention", "norm"])
+    for _ in range(3):
+        dw.step()
+    torch.cuda.synchronize()
+    ms, n = eng.profile_read("attention")
+    assert n == 3 * 2 and 0.0 < ms < 50.0                  # 2 layers
+    assert eng.profile_read("norm")[1] == 3 * (1 + 2 * 2)  # embedding + two per layer
+    assert eng.profile_read("gemm_o")[1] == 0
+    eng.profile_enable(["attention"], every=4)             # launches 0 and 4 of the 6
+    for _ in range(3):
+        dw.step()
+    torch.cuda.synchronize()
+    assert eng.profile_read("attention")[1] == 2
+    eng.profile_enable([])
+    dw.step()
+    torch.cuda.synchronize()
+    assert eng.profile_read("attention")[1] == 0
+    assert torch.equal(l1, dw.logits) and torch.equal(t1, dw.next_tokens)
 
 
 def test_decode_step_can_be_captured_in_a_graph(hx):
