@@ -206,7 +206,7 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
                 for (int kk = 0; kk < D / 32; ++kk)
                     sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]),
                                                                  __builtin_bit_cast(bf16x8_t, qb[kk]), sc, 0, 0, 0);
-                hx_hold_operands(qb);                          // short-lived operands outlive the products that read them
+                hx_hold_operands(qb, kop, sc);                 // short-lived operands outlive the products that read them
                 float s4[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) s4[r] = sc[r] * scale_log2e;
@@ -252,10 +252,7 @@ __device__ __forceinline__ void stream_tiles_chunk(ChunkState<D> &st, const u32x
                     st.o[cb][2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, hi), pop_lo, st.o[cb][2 * q + 1], 0, 0, 0);
                 }
             }
-            if (FP8) {                                         // converted operands outlive the products that read them
-                hx_hold_operands(kop);
-                hx_hold_operands(vv);
-            }
+            if (FP8) hx_hold_operands(vv);                     // converted operands outlive the products that read them
             // the slot is free: request tile i + PF into it (or the query once the run is exhausted)
             const int nx = i + PF;
             const int32_t blk = (nx < 64) ? __builtin_amdgcn_readlane(blk_lo, nx & 63) : __builtin_amdgcn_readlane(blk_hi, nx & 63);

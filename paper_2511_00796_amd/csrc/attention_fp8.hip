@@ -58,7 +58,7 @@ __device__ __forceinline__ void stream_tiles8(AttnState8<D> &st, const bf16x8_t 
                 kop[kk] = u32x4_t{a.x, a.y, b.x, b.y};
                 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kop[kk]), qop[kk], sc, 0, 0, 0);
             }
-            hx_hold_operands(kop);                             // converted operands outlive the products that read them
+            hx_hold_operands(kop, sc);                         // converted operands outlive the products that read them
             float s4[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r >= t0 && tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
@@ -219,8 +219,8 @@ int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, cons
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), e->cfg.n_kv_heads, e->G, scale_log2e,                              \
         (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
-    // ring depths: 128: see the header; 64: depth 6 (depths 2 and 4 gave wrong results on long runs at this head size
-    // for a reason not found in the generated code; 3, 5, 6, 7, 8, 12 are right, and the tests cover long runs)
+    // ring depths: 128: see the header; 64: depth 6 (every depth from 2 to 12 is right since the operand hold is
+    // ordered behind the products; the tests cover long runs)
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 4>), grid, block, 0, st, HX_ATTN8_ARGS);
     else             hipLaunchKernelGGL((attn_splitk_fp8_kernel<64, 6>), grid, block, 0, st, HX_ATTN8_ARGS);
 #undef HX_ATTN8_ARGS

@@ -83,12 +83,32 @@ __device__ __forceinline__ uint2 hx_e4m3x4_to_bf16x4(uint32_t w) {
 // wrote such registers a few issue slots behind the 16x16x32 matrix instruction reading them gave deterministic wrong
 // scores on ragged tiles (gone with every wait forced; gone with the operands held two or more wait states, not with
 // one).  Operands that stay live -- the bf16 kernels multiply straight out of their load registers, and what follows
-// their products closely are accumulator-register reads, which are harmless -- are not exposed.  This keeps
-// short-lived operands live for four wait states past their products.
+// their products closely are accumulator-register reads, which are harmless -- are not exposed.  These statements keep
+// short-lived operands live for four wait states.  The form with `acc` is the one for 16x16x32 products: it also
+// takes the products' accumulator as an in-out operand, which orders it behind the last product of the chain (an
+// asm statement that only names the operands may be scheduled in front of a product that is still to read them --
+// seen in builds with other ring depths, where the add then followed the product directly).
 template <int N>
 __device__ __forceinline__ void hx_hold_operands(const unsigned int __attribute__((ext_vector_type(4))) (&op)[N]) {
     if constexpr (N == 4) asm volatile("s_nop 3" : : "v"(op[0]), "v"(op[1]), "v"(op[2]), "v"(op[3]));
     else if constexpr (N == 2) asm volatile("s_nop 3" : : "v"(op[0]), "v"(op[1]));
+    else static_assert(N == 2 || N == 4, "operand steps of head sizes 64 and 128");
+}
+template <int N>
+__device__ __forceinline__ void hx_hold_operands(const unsigned int __attribute__((ext_vector_type(4))) (&op)[N],
+                                                 f32x4_t &acc) {
+    if constexpr (N == 4) asm volatile("s_nop 3" : "+v"(acc) : "v"(op[0]), "v"(op[1]), "v"(op[2]), "v"(op[3]));
+    else if constexpr (N == 2) asm volatile("s_nop 3" : "+v"(acc) : "v"(op[0]), "v"(op[1]));
+    else static_assert(N == 2 || N == 4, "operand steps of head sizes 64 and 128");
+}
+template <int N>
+__device__ __forceinline__ void hx_hold_operands(const unsigned int __attribute__((ext_vector_type(4))) (&op)[N],
+                                                 const unsigned int __attribute__((ext_vector_type(4))) (&op2)[N],
+                                                 f32x4_t &acc) {
+    if constexpr (N == 4)
+        asm volatile("s_nop 3" : "+v"(acc) : "v"(op[0]), "v"(op[1]), "v"(op[2]), "v"(op[3]), "v"(op2[0]), "v"(op2[1]),
+                     "v"(op2[2]), "v"(op2[3]));
+    else if constexpr (N == 2) asm volatile("s_nop 3" : "+v"(acc) : "v"(op[0]), "v"(op[1]), "v"(op2[0]), "v"(op2[1]));
     else static_assert(N == 2 || N == 4, "operand steps of head sizes 64 and 128");
 }
 
