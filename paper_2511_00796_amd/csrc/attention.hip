@@ -126,6 +126,13 @@ __device__ __forceinline__ void stream_tiles(AttnState<D> &st, const bf16x8_t (&
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk)
                 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ring[s][kk]), qop[kk], sc, 0, 0, 0);
+            if constexpr (D == 64) {
+                // At this head size the compiler reuses a K register of the slot for the mask arithmetic of a ragged
+                // tile a few instructions behind the product that reads it; keep the K operands live past the products
+                // (hx_hold_operands).  At head size 128 nothing writes them before the slot is reloaded.
+                const u32x4_t kheld[2] = {ring[s][0], ring[s][1]};
+                hx_hold_operands(kheld, sc);
+            }
             float s4[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) s4[r] = (tok0 + r >= t0 && tok0 + r < t1) ? sc[r] * scale_log2e : -INFINITY;
