@@ -194,3 +194,54 @@ def test_grouped_attention_equals_row_at_a_time_attention(hx, name, cache, monke
     # layer 0's K and V do not depend on attention: the two caches agree bit for bit there
     per_layer = pools[0].numel() // s.n_layers
     assert torch.equal(pools[0][:per_layer], pools[1][:per_layer])
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_grouped_attention_on_seeded_random_plans(hx, seed, monkeypatch):
+    """Head grouping, head size, KV heads, cache type and the plan of the call (how many sequences, how many keys each
+    already holds, how many consecutive rows each brings, in which order) all drawn from the seed.  The attention
+    output of the first layer must equal the row-at-a-time path's (the decode kernel, held to the oracle by its own
+    tests) up to fp32 reassociation."""
+    rng = np.random.default_rng(500 + seed)
+    d = int(rng.choice([64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    g = int(rng.integers(1, 17))
+    fp8 = bool(rng.integers(0, 2))
+    s = synth.ModelShape("chunk-rnd-%d" % seed, 2, 256, g * n_kv, n_kv, d, 688, 1024)
+    kv_dtype = hx.HX_KV_FP8_E4M3 if fp8 else hx.HX_KV_BF16
+    plan, left = [], 256
+    while left > 0:
+        n = int(min(left, rng.choice([1, 2, 3, 7, 8, 9, 16, 31, 64])))
+        ctx = int(rng.choice([0, 1, 15, 16, 17, 100, 777, 2000])) + int(rng.integers(0, 3))
+        plan.append((ctx, n))
+        left -= n
+    ctx = np.array([c for c, _ in plan], dtype=np.int32)
+    n_new = np.array([n for _, n in plan], dtype=np.int32)
+    final = ctx + n_new
+    table, nb = synth.block_table(final, s.block_size, seed)
+    toks = rng.integers(0, s.vocab, size=256).astype(np.int32)
+    bs = np.concatenate([np.full(n, b) for b, n in enumerate(n_new)])
+    ps = np.concatenate([np.arange(c, c + n) for c, n in plan]).astype(np.int32)
+    seq_start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
+    caps = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("HX_CHUNK_ATTENTION", flag)
+        eng = build(hx, s, seed, 256, int(final.max()) + 1, kv_dtype)
+        kv = hx.KVCache(eng, nb)
+        kv.pool.fill_(0xFF)
+        if int(ctx.sum()) > 0:
+            k, v = synth.kv_fill(s, 0, int(ctx.sum()), seed, device="cuda")
+            kv.prefill_fill(0, k, v, dev(seq_start), dev(table))
+        cap = torch.zeros(s.n_layers, 256, s.q_dim, dtype=torch.float32, device="cuda")
+        eng.set_attn_capture(cap)
+        eng.prefill_chunk(kv, dev(toks), dev(ps), dev(ps + 1), dev(table[bs]))
+        eng.set_attn_capture(None)
+        torch.cuda.synchronize()
+        caps.append(cap[0].cpu().numpy())
+    rowwise, grouped = caps
+    assert np.isfinite(grouped).all()
+    scale = max(float(np.abs(rowwise).max()), 1.0)
+    diff = float(np.abs(grouped - rowwise).max())
+    print("seed %d: d %d, kv heads %d, G %d, %s cache, %d sequences: max |grouped - row-wise| %.2e (max |o| %.2f)"
+          % (seed, d, n_kv, g, "fp8" if fp8 else "bf16", len(plan), diff, scale))
+    assert diff <= 2e-5 * scale, (seed, diff, scale)

@@ -128,6 +128,51 @@ def test_attention_stage_matches_oracle(hx, name, waves, monkeypatch):
     print("attention max abs err", name, worst)
 
 
+@pytest.mark.parametrize("cache", ["bf16", "fp8"])
+@pytest.mark.parametrize("seed", range(6))
+def test_attention_stage_on_seeded_random_shapes(hx, seed, cache, monkeypatch):
+    """Head grouping (1 to 16 query heads per KV head), head size, number of KV heads, batch, length mix (single keys,
+    around block boundaries, hundreds, thousands) and the number of wavefronts all drawn from the seed; both caches;
+    every row against the oracle, to the contract's attention bar."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    g = int(rng.integers(1, 17))
+    batch = int(rng.integers(1, 25))
+    waves = int(rng.choice([64, 256, 2048]))
+    kinds = rng.integers(0, 4, size=batch)
+    lens = np.where(kinds == 0, rng.integers(1, 40, size=batch),
+                    np.where(kinds == 1, rng.integers(1, 9, size=batch) * 16 + rng.integers(-1, 2, size=batch),
+                             np.where(kinds == 2, rng.integers(100, 600, size=batch), rng.integers(1000, 5000, size=batch))))
+    lens = np.maximum(lens, 1).astype(np.int32)
+    monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
+    shape = synth.ModelShape("stage-rnd-%d" % seed, 1, 256, g * n_kv, n_kv, d, 688, 1024)
+    kv_dtype = hx.HX_KV_FP8_E4M3 if cache == "fp8" else hx.HX_KV_BF16
+    eng = hx.Engine(shape, 32, int(lens.max()) + 1, kv_dtype=kv_dtype)
+    table, nb = synth.block_table(lens, 16, seed)
+    k, v = synth.kv_fill(shape, 0, int(lens.sum()), 77 + seed)
+    start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    kv.prefill_fill(0, k.cuda(), v.cuda(), dev(start), dev(table))
+    cfg = oracle.make_config(shape, kv_fp8=cache == "fp8")
+    okv = oracle.PagedKV(cfg, nb)
+    okv.fill(0, synth.as_u16(k), synth.as_u16(v), start, table)
+    q = rng.normal(0, 1.2, size=(batch, shape.q_dim)).astype(np.float32)
+    out = eng.stage_attention(kv, 0, dev(q), dev(lens), dev(table))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    assert np.isfinite(out).all()
+    qr = bits_to_f32(synth.as_u16(torch.from_numpy(q).to(torch.bfloat16)))
+    worst = 0.0
+    for b, T in enumerate(lens):
+        ref = oracle.attention(cfg, qr[b], okv.k[0], okv.v[0], table[b], int(T))
+        worst = max(worst, float(np.abs(out[b] - ref).max()))
+    print("seed %d %s: d %d, kv heads %d, G %d, batch %d, wavefronts %d, keys %d..%d: max abs err %.2e"
+          % (seed, cache, d, n_kv, g, batch, waves, lens.min(), lens.max(), worst))
+    assert worst <= 1e-2, worst
+
+
 def test_attention_is_invariant_to_block_placement_bit_exact(hx):
     shape = STAGE_SHAPES["d128_g7"]
     eng = build_engine(hx, shape, 3, 4, 2048)
