@@ -167,7 +167,8 @@ def main():
 
     if args.prefill:
         P, B, R = args.prefill, 128, 256
-        eng = binding.Engine(s, R, P + 1)
+        kvd = binding.HX_KV_FP8_E4M3 if args.kv_dtype == "fp8" else binding.HX_KV_BF16
+        eng = binding.Engine(s, R, P + 1, kv_dtype=kvd)
         for l in range(s.n_layers):
             eng.pack_layer(l, synth.layer_weights(s, l, wl.seed, device=torch.device("cuda")))
         eng.pack_globals(synth.global_weights(s, wl.seed, device=torch.device("cuda")))
@@ -179,7 +180,7 @@ def main():
         # further engines share the packed weights; each has its own workspace, cache and stream
         lanes = [(eng, kvc, torch.cuda.current_stream())]
         for _ in range(1, n_streams):
-            e2 = binding.Engine(s, R, P + 1, weights=eng.weights)
+            e2 = binding.Engine(s, R, P + 1, kv_dtype=kvd, weights=eng.weights)
             k2 = binding.KVCache(e2, nb)
             k2.pool.zero_()
             lanes.append((e2, k2, torch.cuda.Stream()))
@@ -226,7 +227,8 @@ def main():
                           "value": R * calls / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
                           "rows_per_call": R, "ms_per_call": dt / calls * 1e3,
                           "config": {"workload": "%s-prefill" % s.name, "prompts": B, "prompt_len": P, "rows_per_sequence_per_call": per_seq,
-                                     "streams": n_streams}, "data": "synthetic",
+                                     "streams": n_streams, "kv_cache": "fp8-e4m3" if args.kv_dtype == "fp8" else "bf16"},
+                          "data": "synthetic",
                           "dtype": "bf16",
                           "product_flops_over_call_time_TFLOPs": call_flops / (dt / calls) / 1e12,
                           "roofline": {"kernel": "gemm_stream_kernel (gate|up product, 256 rows)", "bound": "mfma",
