@@ -79,7 +79,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="7b-b128")
+    ap.add_argument("--workload", default="7b-b128",
+                    help="1.5b-b64, 1.5b-b256-longtail, 7b-b128 (default, the configuration the metric is quoted on) or "
+                         "14b-b64; tiny-b4 fits the caches and is a parity case only")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32)
@@ -129,6 +131,10 @@ def main():
         return
 
     binding.load()
+    if args.workload not in synth.WORKLOADS or synth.WORKLOADS[args.workload].kv_fill != "normal":
+        print("bench.py: --workload must be one of %s (tiny-b4 is cache-resident: a parity case, not a bench line)"
+              % ", ".join(n for n, w in synth.WORKLOADS.items() if w.kv_fill == "normal"), file=sys.stderr)
+        sys.exit(2)
     wl = synth.WORKLOADS[args.workload]
     s = wl.shape
     ctx = synth.context_lengths(wl)
