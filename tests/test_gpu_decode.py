@@ -303,8 +303,9 @@ def test_decode_step_can_be_captured_in_a_graph(hx):
         assert torch.equal(dw.logits, ref_logits), i
 
 
-def run_sampled(hx, wl, n_layers, rows, with_floor=False, kv_fp8=False):
-    """kv_fp8: the 8-bit cache variant on both sides."""
+def run_sampled(hx, wl, n_layers, rows, with_floor=False, kv_fp8=False, info=None):
+    """kv_fp8: the 8-bit cache variant on both sides.  info: dict that receives "floor_agreement", the fraction of
+    `rows` on which the oracle and its reordered evaluation pick the same token (with_floor only)."""
     from paper_2511_00796_amd import workload
     shape = wl.shape if n_layers is None else dataclasses.replace(wl.shape, n_layers=n_layers)
     ctx = synth.context_lengths(wl)
@@ -336,6 +337,11 @@ def run_sampled(hx, wl, n_layers, rows, with_floor=False, kv_fp8=False):
         fa = float(np.abs(np.stack([np.stack(alt.attn[r]) for r in rows], axis=1) - ra).max())
         print("%s: reordered-oracle drift: logits %.3e (%.3e of max|logit|), attention %.3e"
               % (wl.name, fl, fl / float(np.abs(rl).max()), fa))
+        if info is not None:
+            info["floor_agreement"] = float(np.mean([alt.next[r] == orc.next[r] for r in rows]))
+            info["floor_logits"] = fl
+            top2 = np.sort(rl, axis=1)[:, -2:]
+            info["mismatch_gaps"] = [float(top2[i, 1] - top2[i, 0]) for i in range(len(rows)) if gt[i] != rt[i]]
     res = compare_step(gl, gt, ga, rl, rt, ra, wl.name, fl, fa)
     # whole-batch properties that hold at any size
     assert torch.isfinite(dw.logits).all()
@@ -372,6 +378,25 @@ def test_degenerate_batches_parity(hx, batch, lo, hi):
     res, _ = run_sampled(hx, wl, 2, list(range(batch)), with_floor=True)
     print("degenerate batch %d [%d,%d]: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f" % ((batch, lo, hi) + res))
     assert res[2] == 1.0
+
+
+def test_full_depth_agreement_of_every_row_against_the_oracles_own_floor(hx):
+    """Config 2 at full size and depth with EVERY row recomputed by the oracle.  At 28 layers two equally valid
+    evaluations of the oracle (matrix products summed in ascending or descending k) differ by ~2e-2 of max|logit| and
+    pick different greedy tokens on some rows -- always rows whose two best logits are nearly tied (on the CPU, at
+    this shape: 9 of 192 rows, 95 %).  So the 99.5 % bar cannot hold per step at full depth for any implementation;
+    what can be required is that every disagreement is such a near-tie -- the oracle's two best logits of the row
+    closer than twice what the oracle's own reordering moves a logit (and, in compare_step, the GPU's token is the
+    oracle's runner-up) -- and that disagreements are about as rare as between the two oracle evaluations."""
+    wl = synth.WORKLOADS["1.5b-b64"]
+    info = {}
+    res, _ = run_sampled(hx, wl, None, list(range(wl.batch)), with_floor=True, info=info)
+    print("1.5b-b64, all %d rows, 28 layers: GPU/oracle agreement %.4f; oracle/reordered-oracle agreement %.4f; "
+          "logit err / max|logit| %.3e, attention err %.3e" % (wl.batch, res[2], info["floor_agreement"], res[0], res[1]))
+    print("top-2 gaps of the rows that disagree: %s; reordered-oracle drift %.3e"
+          % (["%.4f" % g for g in info["mismatch_gaps"]], info["floor_logits"]))
+    assert all(g <= 2 * info["floor_logits"] for g in info["mismatch_gaps"])
+    assert res[2] >= 0.90
 
 
 @pytest.mark.parametrize("cache", ["bf16", "fp8"])
