@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per attention launch at workload 7b-b128 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain
 # copy (profiles/attn_splitk_7b-b128_hbm_traffic.txt).  Valid only for the kernel source they were taken with.
 PMC_TRAFFIC = {"workload": "7b-b128",
-               "attention_hip_sha256": "c4d38a16cd68b26bbaf16624fd2bdfad21f2ed7b4c7c25f4fbf77cad3a3b1ee1",
-               "fetch_bytes": 2165.50e6, "write_bytes": 9.45e6}
+               "attention_hip_sha256": "e0e499a3255909653de10b31ae61b5330752134fa5d3f4cfb9fd2788d1a8c14b",
+               "fetch_bytes": 2165.67e6, "write_bytes": 9.45e6}
 
 
 def measured_traffic(workload_name):

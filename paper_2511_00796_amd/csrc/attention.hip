@@ -4,7 +4,8 @@
 //
 // Work decomposition ("stream-K").  A tile is the K and V of 16 tokens of one KV head.  All tiles of the
 // batch are lined up in (sequence, KV head, block) order and cut into W equal runs of S = ceil(Nt / W)
-// tiles, one run per wavefront, W = 8 per compute unit.  Every wavefront therefore streams the same
+// tiles, one run per wavefront, W = 8 per compute unit (smallish batches: 1024 runs, see step_setup_kernel).
+// Every wavefront therefore streams the same
 // number of bytes whatever the length mix, all of them are resident at once and finish together, and a
 // run is long (about 1 MiB at the 7B shape), so start-up latency is paid once.  A run that crosses from
 // one (sequence, KV head) pair into the next emits one partial result per pair it touches; run w and pair
@@ -51,8 +52,15 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, in
         lens[b] = T;
         for (int i = 256 + b; i < HX_PREFIX_LEN; i += 256) pre[i] = total;
         if (b == 0) {
+            // A run costs its wavefront a schedule look-up, a query load and a partial result (and the combine one
+            // more term per pair), so a smallish batch is cut into 1024 runs (4 per compute unit) instead of one per
+            // wavefront; the other wavefronts exit at once.  Measured at the 1.5B shape (2 KV heads), tiles -> us per
+            // attention launch with 2048 / 1024 runs: 17k 35.0 / 34.5, 35k 56.3 / 54.8, 51k 75.8 / 75.8, 74k 104.8 /
+            // 108.1, 137k 185 / 192 (and the combine 9.7 / 7.5 us); a run count that is not a multiple of the 256
+            // compute units (1088 runs of 32 tiles) was slower than either (61.7 us at 35k).
             const long long nt = (long long)total * n_kv;
-            sched[0] = (int)((nt + n_waves - 1) / n_waves);
+            const long long s_even = (nt + n_waves - 1) / n_waves, s_1024 = (nt + 1023) / 1024;
+            sched[0] = (int)((nt >= 8192 && nt < 45000 && n_waves > 1024) ? s_1024 : s_even);
             sched[1] = (int)nt;
         }
     } else if (positions != nullptr) {
