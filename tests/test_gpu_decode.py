@@ -2,9 +2,9 @@
 
 Bars (the numeric contract of the decode step): max abs logit error <= 2e-2 * max|logit|;
 attention-output max abs error <= 1e-2 in every layer; greedy-token agreement >= 99.5 % per step
-(rows whose oracle top-2 logit gap is below 4x the measured logit error are near-ties where either
-token is a correct argmax of a correctly rounded computation; they are reported, and tolerated only
-if the GPU token is the oracle's runner-up).
+(a row on which the GPU picks another token is a near-tie if the oracle's own logit of that token is
+within 4x the measured logit error of the oracle's maximum: there either token is a correct argmax of a
+correctly rounded computation; such rows are reported, any other disagreement fails).
 
 Depth.  The contract rounds activations to bf16 at seven points per layer.  Two correct fp32
 evaluations that differ only in summation order round a few of those activations differently, and
@@ -54,10 +54,11 @@ def compare_step(gpu_logits, gpu_tokens, gpu_attn, ref_logits, ref_tokens, ref_a
     assert aerr <= max(ATTN_TOL, FLOOR_FACTOR * floor_attn), (what, aerr, floor_attn)
     agree = gpu_tokens == ref_tokens
     for b in np.nonzero(~agree)[0]:
-        top2 = np.sort(ref_logits[b])[-2:]
-        gap = float(top2[1] - top2[0])
-        runner_up = int(np.argsort(ref_logits[b])[-2])
-        assert gap < 4 * lerr and int(gpu_tokens[b]) == runner_up, (what, "row", int(b), "gap", gap, "err", lerr)
+        # a different token is tolerated only among near-ties: the oracle's own logit of the GPU's token must be
+        # within the error bound of the oracle's maximum (usually its runner-up; with 152 k logits a third one can
+        # sit in the same band)
+        deficit = float(ref_logits[b].max() - ref_logits[b][int(gpu_tokens[b])])
+        assert deficit < 4 * lerr, (what, "row", int(b), "deficit", deficit, "err", lerr)
     return lerr / scale, aerr, float(agree.mean())
 
 
@@ -392,8 +393,9 @@ def test_full_depth_agreement_of_every_row_against_the_oracles_own_floor(hx):
     pick different greedy tokens on some rows -- always rows whose two best logits are nearly tied (on the CPU, at
     this shape: 9 of 192 rows, 95 %).  So the 99.5 % bar cannot hold per step at full depth for any implementation;
     what can be required is that every disagreement is such a near-tie -- the oracle's two best logits of the row
-    closer than twice what the oracle's own reordering moves a logit (and, in compare_step, the GPU's token is the
-    oracle's runner-up) -- and that disagreements are about as rare as between the two oracle evaluations."""
+    closer than twice what the oracle's own reordering moves a logit (and, in compare_step, the oracle's logit of the
+    GPU's token within the error bound of its maximum) -- and that disagreements are about as rare as between the two
+    oracle evaluations."""
     wl = synth.WORKLOADS["1.5b-b64"]
     info = {}
     res, _ = run_sampled(hx, wl, None, list(range(wl.batch)), with_floor=True, info=info)
