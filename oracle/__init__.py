@@ -54,6 +54,10 @@ class _Layer(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "bqkv", "wo", "g2", "wg", "wu", "wd")]
 
 
+class _Trace(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("u1", "qkv", "q", "k_new", "v_new", "o", "y_o", "x_mid", "u2", "m", "y_d")]
+
+
 class _Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("gf", C.c_void_p), ("wlm", C.c_void_p), ("layers", C.POINTER(_Layer))]
 
@@ -318,12 +322,23 @@ def attention(cfg: _Config, q, kpool, vpool, table_row, T: int) -> np.ndarray:
 
 
 def layer_step(cfg: _Config, layer: _Layer, x, pos: int, kpool, vpool, table_row,
-               want_attn: bool = False):
-    """One decoder layer for one sequence; x (fp32 [hidden]) is updated in place."""
+               want_attn: bool = False, trace: Optional[dict] = None):
+    """One decoder layer for one sequence; x (fp32 [hidden]) is updated in place.  trace: a dict that receives the
+    layer's intermediate results (u1, qkv, q, k_new, v_new, o, y_o, x_mid, u2, m, y_d: see orc_trace)."""
     assert x.dtype == np.float32 and x.flags.c_contiguous
     attn = np.empty(cfg.n_q_heads * cfg.head_dim, dtype=np.float32) if want_attn else None
-    lib().orc_layer_step(C.byref(cfg), C.byref(layer), _p(x), C.c_int(pos), _p(kpool), _p(vpool),
-                         _p(_i32(table_row)), _p(attn))
+    if trace is None:
+        lib().orc_layer_step(C.byref(cfg), C.byref(layer), _p(x), C.c_int(pos), _p(kpool), _p(vpool),
+                             _p(_i32(table_row)), _p(attn))
+        return attn
+    H, QD, KD = cfg.hidden, cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    sizes = {"u1": H, "qkv": QD + 2 * KD, "q": QD, "k_new": KD, "v_new": KD, "o": QD, "y_o": H, "x_mid": H, "u2": H,
+             "m": cfg.intermediate, "y_d": H}
+    for name, n in sizes.items():
+        trace[name] = np.empty(n, dtype=np.float32)
+    tr = _Trace(*[trace[name].ctypes.data for name, _ in _Trace._fields_])
+    lib().orc_layer_step_trace(C.byref(cfg), C.byref(layer), _p(x), C.c_int(pos), _p(kpool), _p(vpool),
+                               _p(_i32(table_row)), _p(attn), C.byref(tr))
     return attn
 
 

@@ -19,8 +19,10 @@
  *
  * Nothing here is blocked, fused, tiled or reordered.  It shares no code, table or header
  * with the GPU library.  Only tests, the smoke check and the benchmark's CPU-baseline leg call
- * it.  Built with -DORC_SUM_DESCENDING the matrix products add their terms in descending k: an
- * equally valid fp32 evaluation used only to measure how far two correct implementations drift apart.
+ * it.  Built with -DORC_SUM_DESCENDING every sum of the step (matrix products, the norm's mean of squares, the
+ * score dot products, the softmax denominator, the probability-weighted sum of V) adds its terms in descending
+ * instead of ascending index order: an equally valid fp32 evaluation of the same definition, used only to measure
+ * how far two correct implementations drift apart.
  * Parity status: every function is pinned by tests/test_oracle_*.py against closed
  * forms, invariants, numpy / torch library routines and brute-force recomputation; the paper
  * prints no worked numbers for this stage, so there is no golden value from it.
@@ -102,10 +104,18 @@ static uint16_t kv_round(const orc_config *c, float f) {
 
 /* ---- the elementary operations ---------------------------------------------------------- */
 
+/* order in which a sum over i = 0..n-1 adds its terms: ascending (the contract), or descending in the
+   sensitivity variant */
+#ifdef ORC_SUM_DESCENDING
+#define ORC_FOR_SUM(i, n) for (int i = (n) - 1; i >= 0; --i)
+#else
+#define ORC_FOR_SUM(i, n) for (int i = 0; i < (n); ++i)
+#endif
+
 /* y_i = x_i * rsqrt(mean_j x_j^2 + eps) * g_i */
 void orc_rmsnorm(const float *x, const uint16_t *g, int n, float eps, float *y) {
     float ss = 0.0f;
-    for (int i = 0; i < n; ++i) ss += x[i] * x[i];
+    ORC_FOR_SUM(i, n) ss += x[i] * x[i];
     float r = 1.0f / sqrtf(ss / (float)n + eps);
     for (int i = 0; i < n; ++i) y[i] = x[i] * r * orc_bf16_to_f32(g[i]);
 }
@@ -113,11 +123,7 @@ void orc_rmsnorm(const float *x, const uint16_t *g, int n, float eps, float *y) 
 /* y[n] = sum_k x[k] * W[k][n] (+ bias[n]);  W is [K, N] row-major bf16, k ascending */
 void orc_linear(const float *x, const uint16_t *W, const uint16_t *bias, int K, int N, float *y) {
     for (int n = 0; n < N; ++n) y[n] = 0.0f;
-#ifdef ORC_SUM_DESCENDING /* sensitivity variant: the same sums in the opposite order (see tests) */
-    for (int k = K - 1; k >= 0; --k) {
-#else
-    for (int k = 0; k < K; ++k) {
-#endif
+    ORC_FOR_SUM(k, K) {
         const float xk = x[k];
         const uint16_t *w = W + (size_t)k * N;
         for (int n = 0; n < N; ++n) y[n] += xk * orc_bf16_to_f32(w[n]);
@@ -145,7 +151,7 @@ void orc_softmax(const float *s, int n, float *p) {
     for (int i = 1; i < n; ++i)
         if (s[i] > m) m = s[i];
     float sum = 0.0f;
-    for (int i = 0; i < n; ++i) {
+    ORC_FOR_SUM(i, n) {
         p[i] = expf(s[i] - m);
         sum += p[i];
     }
@@ -199,12 +205,12 @@ void orc_attention(const orc_config *c, const float *q, const uint16_t *kpool, c
         for (int t = 0; t < T; ++t) {
             const uint16_t *kr = kpool + kv_index(c, table[t / c->block_size], t % c->block_size, kvh);
             float dot = 0.0f;
-            for (int j = 0; j < d; ++j) dot += q[h * d + j] * orc_bf16_to_f32(kr[j]);
+            ORC_FOR_SUM(j, d) dot += q[h * d + j] * orc_bf16_to_f32(kr[j]);
             s[t] = dot * scale;
         }
         orc_softmax(s, T, p);
         for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;
-        for (int t = 0; t < T; ++t) {
+        ORC_FOR_SUM(t, T) {
             const uint16_t *vr = vpool + kv_index(c, table[t / c->block_size], t % c->block_size, kvh);
             for (int j = 0; j < d; ++j) o[h * d + j] += p[t] * orc_bf16_to_f32(vr[j]);
         }
@@ -218,8 +224,23 @@ void orc_attention(const orc_config *c, const float *q, const uint16_t *kpool, c
 /* x [hidden] is the fp32 residual stream (updated in place).  The new token's K and V are
    written at position `pos` through `table`, then positions 0..pos are attended.
    attn_out (may be NULL) receives o before its rounding. */
-void orc_layer_step(const orc_config *c, const orc_layer *w, float *x, int pos, uint16_t *kpool,
-                    uint16_t *vpool, const int32_t *table, float *attn_out) {
+/* Intermediate results of one layer step, for stage-by-stage comparisons (every pointer may be NULL):
+   u1 [hidden] rounded input of the q/k/v projection; qkv [qkv_dim] projection + bias before the rotation;
+   q [n_q_heads*head_dim] rotated, rounded query; k_new, v_new [n_kv_heads*head_dim] what entered the cache (as fp32);
+   o [n_q_heads*head_dim] attention output before rounding; y_o [hidden] output projection; x_mid [hidden] residual
+   stream after the attention block; u2 [hidden]; m [intermediate] rounded SwiGLU output; y_d [hidden] down projection. */
+typedef struct {
+    float *u1, *qkv, *q, *k_new, *v_new, *o, *y_o, *x_mid, *u2, *m, *y_d;
+} orc_trace;
+
+static void trace_copy(float *dst, const float *src, int n) {
+    if (dst) memcpy(dst, src, sizeof(float) * (size_t)n);
+}
+
+void orc_layer_step_trace(const orc_config *c, const orc_layer *w, float *x, int pos, uint16_t *kpool,
+                          uint16_t *vpool, const int32_t *table, float *attn_out, const orc_trace *tr) {
+    static const orc_trace none = {0};
+    if (!tr) tr = &none;
     int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, I = c->intermediate;
     int QD = nq * d, KD = nkv * d, N = QD + 2 * KD;
     float *u = (float *)malloc(sizeof(float) * (size_t)H);
@@ -232,11 +253,14 @@ void orc_layer_step(const orc_config *c, const orc_layer *w, float *x, int pos, 
     /* attention block */
     orc_rmsnorm(x, w->g1, H, c->rms_eps, u);
     for (int i = 0; i < H; ++i) u[i] = round_act(c, u[i]);
+    trace_copy(tr->u1, u, H);
     orc_linear(u, w->wqkv, c->qkv_bias ? w->bqkv : NULL, H, N, qkv);
+    trace_copy(tr->qkv, qkv, N);
     float *q = qkv, *k = qkv + QD, *v = qkv + QD + KD;
     for (int h = 0; h < nq; ++h) orc_rope(q + h * d, d, pos, c->rope_theta);
     for (int h = 0; h < nkv; ++h) orc_rope(k + h * d, d, pos, c->rope_theta);
     for (int i = 0; i < QD; ++i) q[i] = round_act(c, q[i]);
+    trace_copy(tr->q, q, QD);
     {
         int32_t blk = table[pos / c->block_size];
         int slot = pos % c->block_size;
@@ -245,25 +269,38 @@ void orc_layer_step(const orc_config *c, const orc_layer *w, float *x, int pos, 
             for (int j = 0; j < d; ++j) {
                 kpool[at + j] = kv_round(c, k[h * d + j]);
                 vpool[at + j] = kv_round(c, v[h * d + j]);
+                if (tr->k_new) tr->k_new[h * d + j] = orc_bf16_to_f32(kpool[at + j]);
+                if (tr->v_new) tr->v_new[h * d + j] = orc_bf16_to_f32(vpool[at + j]);
             }
         }
     }
     orc_attention(c, q, kpool, vpool, table, pos + 1, o);
     if (attn_out) memcpy(attn_out, o, sizeof(float) * (size_t)QD);
+    trace_copy(tr->o, o, QD);
     for (int i = 0; i < QD; ++i) o[i] = round_act(c, o[i]);
     orc_linear(o, w->wo, NULL, QD, H, y);
     for (int i = 0; i < H; ++i) x[i] += y[i];
+    trace_copy(tr->y_o, y, H);
+    trace_copy(tr->x_mid, x, H);
 
     /* SwiGLU block */
     orc_rmsnorm(x, w->g2, H, c->rms_eps, u);
     for (int i = 0; i < H; ++i) u[i] = round_act(c, u[i]);
+    trace_copy(tr->u2, u, H);
     orc_linear(u, w->wg, NULL, H, I, gt);
     orc_linear(u, w->wu, NULL, H, I, up);
     for (int i = 0; i < I; ++i) gt[i] = round_act(c, orc_silu(gt[i]) * up[i]);
     orc_linear(gt, w->wd, NULL, I, H, y);
+    trace_copy(tr->m, gt, I);
+    trace_copy(tr->y_d, y, H);
     for (int i = 0; i < H; ++i) x[i] += y[i];
 
     free(u); free(qkv); free(o); free(y); free(gt); free(up);
+}
+
+void orc_layer_step(const orc_config *c, const orc_layer *w, float *x, int pos, uint16_t *kpool,
+                    uint16_t *vpool, const int32_t *table, float *attn_out) {
+    orc_layer_step_trace(c, w, x, pos, kpool, vpool, table, attn_out, NULL);
 }
 
 /* x = embedding row of the token, as fp32 */
@@ -351,13 +388,13 @@ void orc_full_causal(const orc_config *c, const orc_weights *w, const int32_t *t
                 int kvh = h / G;
                 for (int r = 0; r <= t; ++r) { /* causal mask: keys 0..t only */
                     float dot = 0.0f;
-                    for (int j = 0; j < d; ++j)
+                    ORC_FOR_SUM(j, d)
                         dot += Q[(size_t)t * QD + h * d + j] * Km[(size_t)r * KD + kvh * d + j];
                     s[r] = dot * scale;
                 }
                 orc_softmax(s, t + 1, p);
                 for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;
-                for (int r = 0; r <= t; ++r)
+                ORC_FOR_SUM(r, t + 1)
                     for (int j = 0; j < d; ++j) o[h * d + j] += p[r] * Vm[(size_t)r * KD + kvh * d + j];
             }
             if (attn_out) memcpy(attn_out + ((size_t)l * n + t) * QD, o, sizeof(float) * (size_t)QD);
