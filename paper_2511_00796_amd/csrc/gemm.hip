@@ -12,6 +12,7 @@
 // projection; logits + per-tile argmax candidates; logits + per-tile sampling candidates and log-sum-exp pieces.
 #include "hx_internal.h"
 #include <algorithm>
+#include <mutex>
 
 // ---- weight packing ------------------------------------------------------------------------------------------
 // grid (n_tiles, ceil(k_steps / 4)), 256 threads: one wavefront per (n_tile, k_step).
@@ -144,12 +145,12 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
     if (producer) {
         // k-slice w of this workgroup covers k-steps [split0 + w*spw, min(split1, +spw)); chunk c of it is a
         // contiguous run of the packed activations.
-        // Virtual chunk v is real chunk max(v - CPR, 0): the consumers spend their first ring revolution
-        // multiplying zeros (ring not filled yet) with chunk 0, then fall into step with the real chunks.
+        // The consumers spend their first ring revolution (CPR virtual chunks) only requesting weight tiles; real chunk
+        // c is their virtual chunk c + CPR and lives in stage (c + CPR) % NBUF.
         const u32x4_t *xp4 = (const u32x4_t *)a_xp;
         const int last_u4 = a_k_steps * MG * 64 - 1;
         const int pid = wave - NC;
-        auto copy_chunk = [&](int v) {
+        auto copy_chunk = [&](int v) {                       // direct L2 -> LDS copy of virtual chunk v
             const int buf = v % NBUF;
             const int c = max(v - CPR, 0);
 #pragma unroll
@@ -168,13 +169,9 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
         // The copy goes through registers (global load, then LDS store): measured faster than the direct L2 -> LDS
         // path, which slows the weight stream of the same compute unit down when both run (timing lab: weights alone
         // 27 us, direct copy alone 18 us, both 49 us for 60 workgroups).
-        // Chunk v + 2 is requested while chunk v + 1 is stored; n_virtual is even, so the two register sets alternate
-        // statically.  Stage v + 1 is written between the barriers that end chunks v - 1 and v; the buffer it replaces
-        // (chunk v + 1 - NBUF) was released at or before the first of them.
         static_assert(!COPY_VIA_REGISTERS || (RING / KC) % 2 == 0, "register sets alternate in pairs of chunks");
         u32x4_t ra[GG::PVP], rb[GG::PVP];
-        auto load_chunk = [&](int v, u32x4_t (&r)[GG::PVP]) {
-            const int c = max(v - CPR, 0);
+        auto load_chunk = [&](int c, u32x4_t (&r)[GG::PVP]) {
 #pragma unroll
             for (int f = 0; f < GG::PVP; ++f) {
                 const int ff = pid * GG::PVP + f;
@@ -183,8 +180,8 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                 r[f] = xp4[min((kb + c * KC) * MG * 64 + i * 64 + lane, last_u4)];
             }
         };
-        auto store_chunk = [&](int v, const u32x4_t (&r)[GG::PVP]) {
-            const int buf = v % NBUF;
+        auto store_chunk = [&](int c, const u32x4_t (&r)[GG::PVP]) {
+            const int buf = (c + CPR) % NBUF;
 #pragma unroll
             for (int f = 0; f < GG::PVP; ++f) {
                 const int ff = pid * GG::PVP + f;
@@ -192,24 +189,34 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                 xs[(buf * WK + w) * SLICE_U4 + i * 64 + lane] = r[f];
             }
         };
+        // Barrier v ends the consumers' virtual chunk v (one per KC k-steps, CPR of them before the first real chunk:
+        // the revolution that fills their weight ring, which needs no activations).  The barriers of that revolution
+        // but the last are passed at once, so the consumers have requested their whole ring before they first wait
+        // for this wavefront; chunks 0 and 1 are handed over at the last of them, chunk c >= 2 at barrier c + CPR - 2,
+        // one chunk ahead of its use.  Chunk c + 2 is requested as soon as chunk c has left its registers; the two
+        // register sets alternate statically (n_chunks is even).
         load_chunk(0, ra);
         load_chunk(1, rb);
+#pragma unroll
+        for (int i = 0; i < CPR - 1; ++i) __syncthreads();
         store_chunk(0, ra);
-        __syncthreads();
-        for (int v = 0; v < n_virtual; v += 2) {
-            if (v + 2 < n_virtual) load_chunk(v + 2, ra);
-            store_chunk(v + 1, rb);
+        if (2 < n_chunks) load_chunk(2, ra);
+        for (int c = 1; c < n_chunks - 1; c += 2) {
+            store_chunk(c, rb);
+            if (c + 2 < n_chunks) load_chunk(c + 2, rb);
             __syncthreads();
-            if (v + 3 < n_virtual) load_chunk(v + 3, rb);
-            if (v + 2 < n_virtual) store_chunk(v + 2, ra);
+            store_chunk(c + 1, ra);
+            if (c + 3 < n_chunks) load_chunk(c + 3, ra);
             __syncthreads();
         }
+        store_chunk(n_chunks - 1, rb);
+        __syncthreads();
+        __syncthreads();
+        __syncthreads();
         } else {
 #pragma unroll
         for (int q = 0; q < LOOK; ++q) copy_chunk(q);
-        __builtin_amdgcn_s_waitcnt(HX_VMCNT((LOOK - 1) * GG::PVP));   // stage 0 has landed
-        __syncthreads();
-        for (int v = 0; v < n_virtual; ++v) {
+        for (int v = 0; v < n_virtual; ++v) {                    // barrier v ends the consumers' virtual chunk v
             if (v + LOOK < n_virtual) {
                 copy_chunk(v + LOOK);                            // into the stage the consumers left at the last barrier
                 __builtin_amdgcn_s_waitcnt(HX_VMCNT((LOOK - 1) * GG::PVP)); // stage v + 1 has landed
@@ -236,16 +243,17 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
 
-    // The ring starts as zeros and the loop starts one revolution early (c0 = -CPR): that revolution
-    // multiplies zeros while it requests the first RING tiles; from then on step s multiplies the tile
+    // The loop starts one revolution early (c0 = -CPR): that revolution multiplies nothing, it only requests the
+    // first RING tiles (at once: it does not wait for the activations); from then on step s multiplies the tile
     // requested RING steps earlier and then requests the tile of step s + RING into the same slot.
     // There is no separate prologue, so the only loads outstanding at any wait are the ring's own, in order.
     u32x4_t ring[RING];
 #pragma unroll
     for (int r = 0; r < RING; ++r) ring[r] = u32x4_t{0u, 0u, 0u, 0u};
-    __syncthreads();
 
-    for (int c0 = -CPR; c0 < n_chunks; c0 += CPR) {
+    int c_first = -CPR;
+    asm volatile("" : "+s"(c_first));                   // opaque: the ring-filling revolution must not be peeled off the loop
+    for (int c0 = c_first; c0 < n_chunks; c0 += CPR) {
 #pragma unroll
         for (int cc = 0; cc < CPR; ++cc) {
             const int c = c0 + cc;
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
 #pragma unroll
                         for (int g = 0; g < MG; ++g) bnxt[g] = xb[((j + 1) * MG + g) * 64];
                     }
-                    if (s < n_valid) {
+                    if (s >= 0 && s < n_valid) {
                         const bf16x8_t aop = __builtin_bit_cast(bf16x8_t, ring[cc * KC + j]);
 #pragma unroll
                         for (int g = 0; g < MG; ++g)
@@ -291,7 +299,7 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
                         const int t = j * MG + g;
                         const u32x4_t bcur = bq[t % DEPTH];
                         if (t + DEPTH < ITEMS) bq[t % DEPTH] = xb[(t + DEPTH) * 64];
-                        if (s < n_valid)
+                        if (s >= 0 && s < n_valid)
                             acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, __builtin_bit_cast(bf16x8_t, bcur), acc[g], 0, 0, 0);
                     }
                     ring[cc * KC + j] = hx_stream_load(wrow + (size_t)min(s + RING, last) * 64);
@@ -454,12 +462,14 @@ __global__ __launch_bounds__(64 * (WN * WK + GemmGeom<MG, WK>::NP)) void gemm_st
 template <int MG, int WN, int WK, int EPI>
 static int launch_one(dim3 grid, hipStream_t st, const GemmArgs &a) {
     constexpr int lds = gemm_lds_bytes<MG, WN, WK>();
-    static bool configured = false;                      // the opt-in for more than 64 KiB of LDS is per kernel
-    if (!configured) {
-        HX_CHECK_HIP(hipFuncSetAttribute((const void *)gemm_stream_kernel<MG, WN, WK, EPI>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        configured = true;
-    }
+    // the opt-in for more than 64 KiB of LDS is per kernel: once per instantiation, whichever thread comes first
+    static std::once_flag once;
+    static hipError_t configured = hipSuccess;
+    std::call_once(once, [] {
+        configured = hipFuncSetAttribute((const void *)gemm_stream_kernel<MG, WN, WK, EPI>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (configured != hipSuccess) return hx_fail(HX_E_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(configured));
     dim3 block(64 * (WN * WK + GemmGeom<MG, WK>::NP));
     hipLaunchKernelGGL((gemm_stream_kernel<MG, WN, WK, EPI>), grid, block, lds, st, HX_GEMM_ARGS);
     return HX_OK;
@@ -485,19 +495,19 @@ static int launch_shape(int wn, int wk, int epilogue, dim3 grid, hipStream_t st,
 }
 
 // ---- host side: how to cut one product into launches ---------------------------------------------------------------
-// A workgroup occupies a whole compute unit (128 KiB of LDS), so a launch runs in rounds of HX_CUS
-// workgroups and a partly filled last round costs a full one.  Measured on MI355X, wn x 1 shapes (wn n-tiles
+// A workgroup occupies a whole compute unit (128 KiB of LDS), so a launch runs in rounds of as many workgroups as
+// the device has compute units (hx_device_cus) and a partly filled last round costs a full one.  Measured on MI355X, wn x 1 shapes (wn n-tiles
 // sharing one activation stream, 32 KiB stages, a barrier every 8 k-steps) are the fastest.  The planner
 // picks wn in {4, 5, 6} -- and, for products whose consumer kernel sums split partials, the number of
 // K-splits (at most HX_MAX_SPLITS, at least 16 k-steps each) -- that minimises rounds x tiles per
 // workgroup, i.e. the time of the busiest compute unit; ties go to the smaller wn and fewer splits.
 // Example: the 1184 tiles of the 7B gate|up matrix make 296 workgroups of 4 (two rounds on 256 compute
 // units) but 237 workgroups of 5 (one round).  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
-#define HX_CUS 256
 
 struct gemm_launch { int wn, wk, splits, tile0, tiles; };
 
 static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_launch *out) {
+    const int cus = hx_device_cus();
     gemm_launch best{4, 1, 1, 0, n_tiles};
     double best_cost = 1e300;
     int max_s = partial ? HX_MAX_SPLITS : 1;
@@ -506,7 +516,7 @@ static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_lau
         for (int s = 1; s <= max_s; ++s) {
             if (s > 1 && k_steps / s < 16) break;
             const int wgs = ((n_tiles + wn - 1) / wn) * s;
-            const int rounds = (wgs + HX_CUS - 1) / HX_CUS;
+            const int rounds = (wgs + cus - 1) / cus;
             const int sps = (k_steps + s - 1) / s;
             // busiest compute unit: rounds x wn tiles x whole ring revolutions (one more to fill the ring), plus
             // a small charge per split for writing and re-reading its partial tile
