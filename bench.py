@@ -40,9 +40,10 @@ def measured_traffic(workload_name):
 
 
 def cpu_baseline(wl, dw_host, sample_rows, sample_layers, kv_fp8=False):
-    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: `sample_rows`
-    sequences through `sample_layers` layers plus embedding and LM head, then scale the per-layer
-    time to the full depth.  Returns the JSON object."""
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: `sample_rows` sequences through
+    `sample_layers` layers plus embedding and LM head.  Rows are independent and run one per core, so with all layers
+    the figure is simply rows / seconds; with fewer layers the per-layer time is scaled to the full depth (and the
+    sample text says so).  Returns the JSON object."""
     import dataclasses
 
     import numpy as np
@@ -62,6 +63,12 @@ def cpu_baseline(wl, dw_host, sample_rows, sample_layers, kv_fp8=False):
     t0 = time.perf_counter()
     oracle.decode_step(cfg, w, kv, toks, ctx, ctx + 1, table)
     t_layers = time.perf_counter() - t0
+    what = "%d of %d sequences (shortest, longest, seeded random)" % (len(rows), wl.batch)
+    if sample_layers == s.n_layers:
+        return {"value": len(rows) / t_layers, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": "%s through all %d layers, embedding and LM head: one whole oracle step of those rows, %.1f s of CPU "
+                          "work; rows are independent, tokens/s = rows / seconds, nothing extrapolated"
+                          % (what, s.n_layers, t_layers)}
     cfg0 = oracle.make_config(dataclasses.replace(s, n_layers=0))
     t0 = time.perf_counter()
     oracle.decode_step(cfg0, w, kv, toks, ctx, ctx + 1, table)
@@ -69,9 +76,8 @@ def cpu_baseline(wl, dw_host, sample_rows, sample_layers, kv_fp8=False):
     per_layer = max(t_layers - t_head, 0.0) / sample_layers
     full = per_layer * s.n_layers + t_head
     return {"value": len(rows) / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d of %d sequences (shortest, longest, seeded random) through %d of %d layers + embedding and "
-                      "LM head, %.1f s of CPU work; per-layer time scaled to %d layers"
-                      % (len(rows), wl.batch, sample_layers, s.n_layers, t_layers + t_head, s.n_layers)}
+            "sample": "%s through %d of %d layers + embedding and LM head, %.1f s of CPU work; per-layer time scaled to %d layers"
+                      % (what, sample_layers, s.n_layers, t_layers + t_head, s.n_layers)}
 
 
 def main():
@@ -84,8 +90,10 @@ def main():
                          "14b-b64; tiny-b4 fits the caches and is a parity case only")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=32)
-    ap.add_argument("--cpu-layers", type=int, default=8)
+    ap.add_argument("--cpu-rows", type=int, default=16,
+                    help="sequences the CPU baseline recomputes (default 16: one per host core of the GPU box, ~20 s of CPU work "
+                         "at 7B; 128 = the whole batch, ~2 min)")
+    ap.add_argument("--cpu-layers", type=int, default=0, help="layers of the CPU baseline (default 0 = all)")
     ap.add_argument("--sample", type=float, default=0.0, metavar="T",
                     help="time decode_step_sample at this temperature instead of the greedy step (reported as such)")
     ap.add_argument("--top-p", type=float, default=1.0, metavar="P",
@@ -138,6 +146,8 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     s = wl.shape
     ctx = synth.context_lengths(wl)
+    if args.cpu_layers <= 0 or args.cpu_layers > s.n_layers:
+        args.cpu_layers = s.n_layers
 
     # rows and layers the CPU baseline will recompute (copied to the host while the workload is built)
     host = None

@@ -129,7 +129,9 @@ int hx_weights_pack(hx_engine *engine, int tensor_kind, int layer, const void *s
 
 /* ---- paged KV cache ------------------------------------------------------------------------------ */
 
-/* Wraps a caller-owned DEVICE pool (256-byte aligned, >= hx_kv_bytes(num_blocks)) as a paged
+/* The KV cache of rollout generation (the memory-bound inference stage of paper Section 1 and Section 3,
+   Observation 1; response lengths are skewed, Section 4.2.2, hence paging).
+   Wraps a caller-owned DEVICE pool (256-byte aligned, >= hx_kv_bytes(num_blocks)) as a paged
    cache of `num_blocks` blocks of 16 tokens.  Pool layout: [layer][block][kv_head][K tile | V tile];
    a tile holds the 16 x head_dim bf16 values of one block and KV head in matrix-core operand
    order, so one wavefront load instruction covers 1 KiB of contiguous memory.  The content is
@@ -137,7 +139,8 @@ int hx_weights_pack(hx_engine *engine, int tensor_kind, int layer, const void *s
 int kv_alloc(hx_engine *engine, void *kv_dev, size_t kv_bytes, int64_t num_blocks, hx_kv **out);
 int kv_free(hx_kv *kv);
 
-/* Scatters caller-supplied K and V of ONE layer into the pool.  k_dev / v_dev: DEVICE bf16
+/* Fills the cache of sequences whose context already exists (a rollout starts from its prompt: paper Section 1,
+   stage (i) of the workflow).  Scatters caller-supplied K and V of ONE layer into the pool.  k_dev / v_dev: DEVICE bf16
    [total_tokens, n_kv_heads, head_dim], the sequences concatenated in batch order;
    seq_start_dev: DEVICE int32 [batch + 1], token offset of each sequence (seq_start[batch] =
    total_tokens); token p of sequence b goes to block block_table[b][p / 16], slot p % 16.
@@ -154,7 +157,9 @@ int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_dev,
 
 /* ---- the decode step ------------------------------------------------------------------------------ */
 
-/* One autoregressive step for `batch` sequences.  All array arguments are DEVICE pointers.
+/* The hot path: one step of rollout generation, which the paper characterises as HBM-I/O-bound inference
+   dominating the workflow (Section 1; Section 3, Observation 1; Section 5.3, Discussion), for the decoder family of
+   Section 5.2.  One autoregressive step for `batch` sequences.  All array arguments are DEVICE pointers.
      tokens      int32 [batch]   id of the token to process for each sequence
      positions   int32 [batch]   its position = number of tokens already cached
      seq_lens    int32 [batch]   keys attended = positions + 1 (the new token attends itself)
@@ -249,7 +254,8 @@ int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention 
 
 /* Tuning knobs read from the environment (none is needed for correct or fast operation; results stay within the
    same tolerances, only summation order changes):
-     HX_ATTN_WAVES=n        wavefronts of the attention kernel, read at hx_engine_create (default 2048 = 8 per CU)
+     HX_ATTN_WAVES=n        wavefronts of the attention kernel, read at hx_engine_create (default 8 per compute unit
+                            of the device: 2048 on an MI355X)
      HX_GEMM_SHAPE=wn,wk,s  force tiles per workgroup (4..6, or 4 with wk = 2), k-slices per workgroup and K-splits
      HX_GEMM_MAX_SPLITS=s   upper bound of the planner's K-splits (1..9)
      HX_CHUNK_ATTENTION=0   prefill_chunk attends every row on its own (the decode step's kernel) instead of in groups

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 // ---- errors ------------------------------------------------------------------------------------------------------
@@ -54,8 +55,23 @@ static int check_config(const hx_model_config *c) {
     return HX_OK;
 }
 
-static int attention_waves() {      // HX_ATTN_WAVES overrides (tuning)
-    int w = env_int("HX_ATTN_WAVES", 2048);
+// Compute units of the current device, asked once; 256 (an MI355X) where no device can be asked, so that the size
+// queries and the launch planner also answer on a host without a GPU.
+int hx_device_cus() {
+    static std::once_flag once;
+    static int cus = 256;
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        (void)hipGetLastError();
+    });
+    return cus;
+}
+
+static int attention_waves() {      // 8 wavefronts per compute unit (all resident at once); HX_ATTN_WAVES overrides (tuning)
+    int w = env_int("HX_ATTN_WAVES", 8 * hx_device_cus());
     if (w < 64) w = 64;
     if (w > 16384) w = 16384;
     return w;

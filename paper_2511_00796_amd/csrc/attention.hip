@@ -134,11 +134,14 @@ __device__ __forceinline__ void stream_tiles(AttnState<D> &st, const bf16x8_t (&
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk)
                 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ring[s][kk]), qop[kk], sc, 0, 0, 0);
-            if constexpr (D == 64) {
-                // At this head size the compiler reuses a K register of the slot for the mask arithmetic of a ragged
-                // tile a few instructions behind the product that reads it; keep the K operands live past the products
-                // (hx_hold_operands).  At head size 128 nothing writes them before the slot is reloaded.
-                const u32x4_t kheld[2] = {ring[s][0], ring[s][1]};
+            {
+                // The K operands of the slot die with these products, so the compiler may hand their registers to the
+                // next vector instruction (at head size 64 it did: the mask arithmetic of a ragged tile, a few
+                // instructions behind the product that was still to read them).  Keep them live past the products
+                // (hx_hold_operands) at both head sizes.
+                u32x4_t kheld[D / 32];
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) kheld[kk] = ring[s][kk];
                 hx_hold_operands(kheld, sc);
             }
             float s4[4];

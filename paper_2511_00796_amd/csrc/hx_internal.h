@@ -45,6 +45,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 // ---- error reporting (api.hip) -------------------------------------------------------------------
 int hx_fail(int code, const char *fmt, ...);
+int hx_device_cus();   // compute units of the current device (256 where none can be asked)
 #define HX_CHECK_HIP(expr)                                                                         \
     do {                                                                                           \
         hipError_t e_ = (expr);                                                                    \
@@ -201,7 +202,7 @@ struct hx_engine {
     hx_model_config cfg;
     int G, D, q_dim, kv_dim, qkv_dim;
     int m_groups_max;       // ceil(max_batch / 32)
-    int attn_waves;         // wavefronts of the attention kernel (8 per compute unit)
+    int attn_waves;         // wavefronts of the attention kernel (8 per compute unit of the device)
     bool chunk_attention;     // prompt rows of one sequence share a K/V stream (HX_CHUNK_ATTENTION=0 disables)
     int chunk_rows;           // rows per group: min(HX_CHUNK_ROWS, 64 / G)
     char *weights;          // device

@@ -1,19 +1,7 @@
-"""End-to-end GPU parity of decode_step against the CPU oracle on the same seeded inputs.
-
-Bars (the numeric contract of the decode step): max abs logit error <= 2e-2 * max|logit|;
-attention-output max abs error <= 1e-2 in every layer; greedy-token agreement >= 99.5 % per step
-(a row on which the GPU picks another token is a near-tie if the oracle's own logit of that token is
-within 4x the measured logit error of the oracle's maximum: there either token is a correct argmax of a
-correctly rounded computation; such rows are reported, any other disagreement fails).
-
-Depth.  The contract rounds activations to bf16 at seven points per layer.  Two correct fp32
-evaluations that differ only in summation order round a few of those activations differently, and
-the random-weight network amplifies each flip, so their logits drift apart with depth: the oracle
-against ITSELF with its matrix products summed in descending instead of ascending k differs by
-1.0-1.7e-2 * max|logit| at 28 layers (tests/test_oracle_sensitivity.py shows the mechanism on the
-CPU).  The full-depth tests therefore also run that second oracle on the same rows and accept a GPU
-deviation up to the larger of the contract bar and FLOOR_FACTOR x the oracle-vs-oracle drift; both
-numbers are printed.  The 2-layer cases are held to the contract bars alone."""
+"""End-to-end GPU parity of decode_step against the CPU oracle on the same seeded inputs: the tiny configuration
+(every prompt and decode step), prompt chunks, determinism and graph capture, and the mid-size and degenerate batches
+on 2 layers of the 1.5B shape.  The bars and the use of the reordered oracle are stated in tests/parity.py; the
+full-size workloads are in tests/test_gpu_fullsize.py.  Everything here is held to the contract bars alone."""
 import dataclasses
 
 import numpy as np
@@ -22,13 +10,10 @@ import torch
 
 import oracle
 from paper_2511_00796_amd import synth
-from util import OracleRows, host_model
+from parity import ATTN_TOL, LOGIT_TOL, TIE_REL, assert_tokens_agree_like_the_oracles_evaluations, compare_step, run_sampled
+from util import host_model
 
 pytestmark = pytest.mark.gpu
-
-LOGIT_TOL = 2e-2
-ATTN_TOL = 1e-2
-FLOOR_FACTOR = 2.0
 
 
 @pytest.fixture(scope="module")
@@ -43,23 +28,10 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def compare_step(gpu_logits, gpu_tokens, gpu_attn, ref_logits, ref_tokens, ref_attn, what,
-                 floor_logits=0.0, floor_attn=0.0):
-    """Apply the three bars to one step; returns (logit err / max|logit|, attn err, strict agreement).
-    floor_*: drift of the reordered oracle from the oracle on the same rows (0: contract bars only)."""
-    scale = float(np.abs(ref_logits).max())
-    lerr = float(np.abs(gpu_logits - ref_logits).max())
-    assert lerr <= max(LOGIT_TOL * scale, FLOOR_FACTOR * floor_logits), (what, lerr, scale, floor_logits)
-    aerr = float(np.abs(gpu_attn - ref_attn).max())
-    assert aerr <= max(ATTN_TOL, FLOOR_FACTOR * floor_attn), (what, aerr, floor_attn)
-    agree = gpu_tokens == ref_tokens
-    for b in np.nonzero(~agree)[0]:
-        # a different token is tolerated only among near-ties: the oracle's own logit of the GPU's token must be
-        # within the error bound of the oracle's maximum (usually its runner-up; with 152 k logits a third one can
-        # sit in the same band)
-        deficit = float(ref_logits[b].max() - ref_logits[b][int(gpu_tokens[b])])
-        assert deficit < 4 * lerr, (what, "row", int(b), "deficit", deficit, "err", lerr)
-    return lerr / scale, aerr, float(agree.mean())
+def same_token_or_fp32_tie(ref_row, gpu_token):
+    """Without a reordered oracle at hand a different token is accepted only where the oracle's own logits of the two
+    tokens tie to fp32 rounding."""
+    return float(ref_row.max() - ref_row[int(gpu_token)]) <= TIE_REL * float(np.abs(ref_row).max())
 
 
 def test_tiny_config_prompt_then_16_greedy_steps(hx):
@@ -81,7 +53,7 @@ def test_tiny_config_prompt_then_16_greedy_steps(hx):
         eng.pack_layer(l, synth.layer_weights(s, l, wl.seed))
     eng.pack_globals(synth.global_weights(s, wl.seed))
     kv = hx.KVCache(eng, nb)
-    okv = oracle.PagedKV(cfg, nb)
+    okv, akv = oracle.PagedKV(cfg, nb), oracle.PagedKV(cfg, nb)     # the oracle's cache and its reordered evaluation's
     cap = torch.empty(s.n_layers, wl.batch, s.q_dim, dtype=torch.float32, device="cuda")
     eng.set_attn_capture(cap)
 
@@ -97,11 +69,16 @@ def test_tiny_config_prompt_then_16_greedy_steps(hx):
         eng.decode_step(kv, t_d, p_d, s_d, dev(table[rows]), logits, nxt)
         torch.cuda.synchronize()
         rl, rn, ra = oracle.decode_step(cfg, ow, okv, toks, pos, pos + 1, table[rows], want_attn=True)
+        with oracle.descending_sums():      # the same tokens (the oracle's) through the reordered evaluation, its own cache
+            al, an, aa = oracle.decode_step(cfg, ow, akv, toks, pos, pos + 1, table[rows], want_attn=True)
         ga = cap[:, : len(rows)].cpu().numpy() if len(rows) == wl.batch else \
             cap.reshape(-1)[: s.n_layers * len(rows) * s.q_dim].reshape(s.n_layers, len(rows), s.q_dim).cpu().numpy()
-        l, a, ag = compare_step(logits.cpu().numpy(), nxt.cpu().numpy(), ga, rl, rn, ra, ("pos", pos.tolist()))
-        worst_l, worst_a = max(worst_l, l), max(worst_a, a)
-        agree.append(ag)
+        # contract bars alone; the reordered oracle only decides whether a differing token is a near-tie (4 rows: the
+        # pooled-error ratio of single steps is not meaningful)
+        rep = compare_step(logits.cpu().numpy(), nxt.cpu().numpy(), ga, rl, rn, ra, "tiny, positions %s" % pos.tolist(),
+                           al, an, aa, rms_factor=None, quiet=True)
+        worst_l, worst_a = max(worst_l, rep.logit_err), max(worst_a, rep.attn_err)
+        agree.append(rep.agreement)
         return rn
 
     # prompt: position p for every sequence that still has prompt tokens left
@@ -165,7 +142,7 @@ def test_chunked_prompt_processing_matches_dense_causal_recomputation(hx):
         assert err <= LOGIT_TOL * scale, (b, err, scale)
         worst = max(worst, err / scale)
         first[b] = int(np.argmax(ref))
-        assert int(nxt[b]) == first[b] or np.sort(ref)[-1] - np.sort(ref)[-2] < 4 * err
+        assert same_token_or_fp32_tie(ref, nxt[b])
     # the oracle's own cache, built position by position, for the steps that follow
     okv = oracle.PagedKV(cfg, nb)
     for p in range(int(ctx.max())):
@@ -226,8 +203,7 @@ def test_chunked_prompt_processing_with_256_row_chunks(hx):
         err = float(np.abs(gl[b] - ref).max())
         assert err <= LOGIT_TOL * scale, (b, err, scale)
         worst = max(worst, err / scale)
-        top2 = np.sort(ref)[-2:]
-        assert int(nxt[b]) == int(np.argmax(ref)) or top2[1] - top2[0] < 4 * err
+        assert same_token_or_fp32_tie(ref, nxt[b])
     print("256-row prompt chunks: worst logit err / max|logit| %.3e" % worst)
 
 
@@ -304,107 +280,25 @@ def test_decode_step_can_be_captured_in_a_graph(hx):
         assert torch.equal(dw.logits, ref_logits), i
 
 
-def run_sampled(hx, wl, n_layers, rows, with_floor=False, kv_fp8=False, info=None):
-    """kv_fp8: the 8-bit cache variant on both sides.  info: dict that receives "floor_agreement", the fraction of
-    `rows` on which the oracle and its reordered evaluation pick the same token (with_floor only)."""
-    from paper_2511_00796_amd import workload
-    shape = wl.shape if n_layers is None else dataclasses.replace(wl.shape, n_layers=n_layers)
-    ctx = synth.context_lengths(wl)
-    seq_start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int64)
-    tokens = synth.token_ids(wl, wl.batch)
-    orc = OracleRows(shape, rows, ctx, seq_start, tokens, kv_fp8=kv_fp8)
-    alt = OracleRows(shape, rows, ctx, seq_start, tokens, descending=True, kv_fp8=kv_fp8) if with_floor else None
-
-    def tap(kind, layer, t):
-        orc.tap(kind, layer, t)
-        if alt:
-            alt.tap(kind, layer, t)
-    dw = workload.build(wl, n_layers=n_layers, tap=tap, kv_dtype=hx.HX_KV_FP8_E4M3 if kv_fp8 else hx.HX_KV_BF16)
-    orc.finish()
-    cap = torch.empty(shape.n_layers, wl.batch, shape.q_dim, dtype=torch.float32, device="cuda")
-    dw.engine.set_attn_capture(cap)
-    dw.step()
-    torch.cuda.synchronize()
-    gl = dw.logits[rows].cpu().numpy()
-    gt = dw.next_tokens[rows].cpu().numpy()
-    ga = cap[:, rows].cpu().numpy()
-    rl = np.stack([orc.logits[r] for r in rows])
-    rt = np.array([orc.next[r] for r in rows], dtype=np.int32)
-    ra = np.stack([np.stack(orc.attn[r]) for r in rows], axis=1)
-    fl = fa = 0.0
-    if alt:
-        alt.finish()
-        fl = float(np.abs(np.stack([alt.logits[r] for r in rows]) - rl).max())
-        fa = float(np.abs(np.stack([np.stack(alt.attn[r]) for r in rows], axis=1) - ra).max())
-        print("%s: reordered-oracle drift: logits %.3e (%.3e of max|logit|), attention %.3e"
-              % (wl.name, fl, fl / float(np.abs(rl).max()), fa))
-        if info is not None:
-            info["floor_agreement"] = float(np.mean([alt.next[r] == orc.next[r] for r in rows]))
-            info["floor_logits"] = fl
-            top2 = np.sort(rl, axis=1)[:, -2:]
-            info["mismatch_gaps"] = [float(top2[i, 1] - top2[i, 0]) for i in range(len(rows)) if gt[i] != rt[i]]
-    res = compare_step(gl, gt, ga, rl, rt, ra, wl.name, fl, fa)
-    # whole-batch properties that hold at any size
-    assert torch.isfinite(dw.logits).all()
-    assert torch.equal(dw.next_tokens.long(), torch.argmax(dw.logits, dim=1))
-    return res, dw
-
-
-def sample_rows(wl, extra=4):
-    ctx = synth.context_lengths(wl)
-    rows = {int(np.argmin(ctx)), int(np.argmax(ctx))}
-    rng = np.random.default_rng(wl.seed)
-    while len(rows) < min(wl.batch, extra + 2):
-        rows.add(int(rng.integers(0, wl.batch)))
-    return sorted(rows)
-
-
 def test_mid_size_full_batch_parity(hx):
     """1.5B-shaped layers (2 of them), batch 64, KV lengths uniform in [512, 8192], shuffled block table:
-    EVERY row compared (several attention chunks per row, ragged tails, two m-groups in the products)."""
+    EVERY row compared (several attention runs per row, ragged tails, two m-groups in the products), contract bars
+    alone.  One row of 64 is 1.6 %, so the 99.5 % bar means every row -- except rows that are near-ties by the
+    oracle's own logits (parity.py), about as many as between the oracle's two evaluations."""
     wl = synth.WORKLOADS["1.5b-b64"]
-    info = {}
-    res, _ = run_sampled(hx, wl, 2, list(range(wl.batch)), with_floor=True, info=info)
-    print("mid-size: logit err / max|logit| %.3e, attn err %.3e, strict agreement %.4f" % res)
-    print("mid-size: top-2 gaps of rows that disagree %s; reordered-oracle drift %.3e, its agreement %.4f"
-          % (["%.5f" % g for g in info["mismatch_gaps"]], info["floor_logits"], info["floor_agreement"]))
-    # one row of 64 is 1.6 %: the 99.5 % bar means every row, except rows whose two best logits are closer than the
-    # oracle's own reordering moves a logit (there either token is a correct greedy choice)
-    assert all(g <= 2 * info["floor_logits"] for g in info["mismatch_gaps"])
-    assert res[2] >= 0.95
+    rep, _, _ = run_sampled(hx, wl, 2, list(range(wl.batch)), with_floor=True)
+    assert_tokens_agree_like_the_oracles_evaluations(rep, wl.batch)
 
 
 @pytest.mark.parametrize("batch,lo,hi", [(1, 16384, 16384), (2, 1, 1), (3, 15, 17)])
 def test_degenerate_batches_parity(hx, batch, lo, hi):
     """Extremes of the attention schedule on 1.5B-shaped layers (2 of them): ONE sequence at the maximum length (its
     2 x 1025 tiles spread over the 2048 wavefronts, a few tiles each, most wavefronts idle), sequences with a single
-    cached token (two keys), and lengths around one block.  With two keys nothing averages out: the second layer's
-    attention output moves by 6-8e-3 between the oracle and its own reordered evaluation (|o| ~ 2.5), so the floor of
-    the reordered oracle is taken into account as in the full-depth tests; the first layer agrees to 4e-6."""
+    cached token (two keys), and lengths around one block.  Contract bars alone; with so few rows the pooled-error
+    criterion is not applied (a ratio of two maxima of a handful of rounding events)."""
     wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=batch, lo=lo, hi=hi)
-    res, _ = run_sampled(hx, wl, 2, list(range(batch)), with_floor=True)
-    print("degenerate batch %d [%d,%d]: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f" % ((batch, lo, hi) + res))
-    assert res[2] == 1.0
-
-
-def test_full_depth_agreement_of_every_row_against_the_oracles_own_floor(hx):
-    """Config 2 at full size and depth with EVERY row recomputed by the oracle.  At 28 layers two equally valid
-    evaluations of the oracle (matrix products summed in ascending or descending k) differ by ~2e-2 of max|logit| and
-    pick different greedy tokens on some rows -- always rows whose two best logits are nearly tied (on the CPU, at
-    this shape: 9 of 192 rows, 95 %).  So the 99.5 % bar cannot hold per step at full depth for any implementation;
-    what can be required is that every disagreement is such a near-tie -- the oracle's two best logits of the row
-    closer than twice what the oracle's own reordering moves a logit (and, in compare_step, the oracle's logit of the
-    GPU's token within the error bound of its maximum) -- and that disagreements are about as rare as between the two
-    oracle evaluations."""
-    wl = synth.WORKLOADS["1.5b-b64"]
-    info = {}
-    res, _ = run_sampled(hx, wl, None, list(range(wl.batch)), with_floor=True, info=info)
-    print("1.5b-b64, all %d rows, 28 layers: GPU/oracle agreement %.4f; oracle/reordered-oracle agreement %.4f; "
-          "logit err / max|logit| %.3e, attention err %.3e" % (wl.batch, res[2], info["floor_agreement"], res[0], res[1]))
-    print("top-2 gaps of the rows that disagree: %s; reordered-oracle drift %.3e"
-          % (["%.4f" % g for g in info["mismatch_gaps"]], info["floor_logits"]))
-    assert all(g <= 2 * info["floor_logits"] for g in info["mismatch_gaps"])
-    assert res[2] >= 0.90
+    rep, _, _ = run_sampled(hx, wl, 2, list(range(batch)), with_floor=True, rms_factor=None)
+    assert rep.agreement == 1.0
 
 
 @pytest.mark.parametrize("cache", ["bf16", "fp8"])
@@ -413,23 +307,9 @@ def test_sequences_far_longer_than_the_benchmarks(hx, waves, cache, monkeypatch)
     """Two sequences of 150 000 to 200 000 keys (up to 12 501 blocks in a table row) on 1.5B-shaped layers (2 of
     them).  With the default 2048 wavefronts a run is ~11 tiles; with 64 wavefronts a run is ~340 tiles of one
     (sequence, head) pair, which takes the block ids in several loads of 128 and ends on a ragged one.  cache = fp8:
-    the 8-bit cache variant and its kernel, on both sides."""
+    the 8-bit cache variant and its kernel, on both sides.  Contract bars alone."""
     monkeypatch.setenv("HX_ATTN_WAVES", str(waves))
     wl = dataclasses.replace(synth.WORKLOADS["1.5b-b64"], batch=2, lo=150000, hi=200000)
-    res, dw = run_sampled(hx, wl, 2, [0, 1], with_floor=True, kv_fp8=cache == "fp8")
+    rep, dw, _ = run_sampled(hx, wl, 2, [0, 1], with_floor=True, kv_fp8=cache == "fp8", rms_factor=None)
     assert dw.engine.attention_waves() == waves
-    print("long sequences, %s cache, %d wavefronts: logit err / max|logit| %.3e, attn err %.3e, agreement %.3f"
-          % ((cache, waves) + res))
-    assert res[2] == 1.0
-
-
-@pytest.mark.parametrize("name", ["1.5b-b64", "1.5b-b256-longtail", "7b-b128", "14b-b64"])
-def test_full_size_sampled_rows_parity(hx, name):
-    """Configs 2-5 at full size, in the launch configuration the benchmark times: the oracle recomputes
-    the shortest, the longest and four seeded random rows through all layers (rows are independent);
-    the remaining rows are covered by properties (finite logits, token = argmax of the row)."""
-    wl = synth.WORKLOADS[name]
-    rows = sample_rows(wl)
-    res, dw = run_sampled(hx, wl, None, rows, with_floor=True)
-    print("%s rows %s: logit err / max|logit| %.3e, attn err %.3e, strict agreement %.4f" % ((name, rows) + res))
-    assert res[2] >= 0.995 or len(rows) < 200   # a near-tie among 6 sampled rows is reported by compare_step
+    assert rep.agreement == 1.0

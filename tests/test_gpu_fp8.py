@@ -13,7 +13,7 @@ import torch
 
 import oracle
 from paper_2511_00796_amd import synth
-from test_gpu_decode import ATTN_TOL, LOGIT_TOL, run_sampled, sample_rows
+from parity import ATTN_TOL, LOGIT_TOL, assert_tokens_agree_like_the_oracles_evaluations, run_sampled, sample_rows
 from util import bits_to_f32, host_model
 
 pytestmark = pytest.mark.gpu
@@ -168,8 +168,8 @@ def test_tiny_model_decodes_through_the_8_bit_cache(hx):
 def test_mid_size_full_batch_parity_with_8_bit_cache(hx):
     """1.5B-shaped layers (2 of them), batch 64, KV lengths uniform in [512, 8192]: every row against the oracle."""
     wl = synth.WORKLOADS["1.5b-b64"]
-    res, _ = run_sampled(hx, wl, 2, list(range(wl.batch)), kv_fp8=True)
-    print("mid-size, 8-bit cache: logit err / max|logit| %.3e, attn err %.3e, strict agreement %.4f" % res)
+    rep, _, _ = run_sampled(hx, wl, 2, list(range(wl.batch)), with_floor=True, kv_fp8=True)
+    assert_tokens_agree_like_the_oracles_evaluations(rep, wl.batch)
 
 
 def test_full_size_7b_batch_128_with_8_bit_cache(hx):
@@ -177,8 +177,8 @@ def test_full_size_7b_batch_128_with_8_bit_cache(hx):
     (with the reordered-oracle drift as the floor, as for the bf16 cache)."""
     wl = synth.WORKLOADS["7b-b128"]
     rows = sample_rows(wl)
-    res, dw = run_sampled(hx, wl, None, rows, with_floor=True, kv_fp8=True)
-    print("7b-b128, 8-bit cache, rows %s: logit err / max|logit| %.3e, attn err %.3e, strict agreement %.4f" % ((rows,) + res))
+    rep, dw, _ = run_sampled(hx, wl, None, rows, with_floor=True, floor_in_bars=True, kv_fp8=True)
+    assert_tokens_agree_like_the_oracles_evaluations(rep, len(rows))
     del dw
     torch.cuda.empty_cache()
 

@@ -1,13 +1,18 @@
 """What a rollout server does around the step, shown on the GPU through the C ABI: response groups sharing the
 physical blocks of their prompt, sequences leaving and joining between steps, and a new policy version packed
-into a live engine.  All of it rests on decode_step being a pure function of (weights, cache contents, inputs)."""
+into a live engine.  All of it rests on decode_step being a pure function of (weights, cache contents, inputs).
+Each feature is checked twice: against the CPU oracle given the same block table / batch / weights (contract bars,
+tokens equal), and for the bit-identity the feature promises between two ways of running the GPU path."""
 import dataclasses
 
 import numpy as np
 import pytest
 import torch
 
+import oracle
 from paper_2511_00796_amd import synth
+from parity import compare_step
+from util import host_model
 
 pytestmark = pytest.mark.gpu
 
@@ -35,14 +40,35 @@ def engine_with(hx, seed, max_batch=16, max_seq_len=512):
     return eng
 
 
-def step(eng, kv, tokens, ctx, table):
+def step(eng, kv, tokens, ctx, table, want_attn=False):
     B = len(ctx)
     logits = torch.empty(B, SHAPE.vocab, dtype=torch.float32, device="cuda")
     nxt = torch.empty(B, dtype=torch.int32, device="cuda")
     ctx = np.asarray(ctx, dtype=np.int32)
+    cap = torch.empty(SHAPE.n_layers, B, SHAPE.q_dim, dtype=torch.float32, device="cuda") if want_attn else None
+    eng.set_attn_capture(cap)
     eng.decode_step(kv, dev(np.asarray(tokens, np.int32)), dev(ctx), dev(ctx + 1), dev(table), logits, nxt)
     torch.cuda.synchronize()
-    return logits.cpu(), nxt.cpu()
+    eng.set_attn_capture(None)
+    return (logits.cpu(), nxt.cpu(), cap.cpu()) if want_attn else (logits.cpu(), nxt.cpu())
+
+
+def oracle_step(seed, data, start, table, n_blocks, tokens, ctx):
+    """The oracle's step for the model of `seed` over a cache it fills itself from the same K/V rows through the same
+    block table (any table: shared blocks are simply written once per sequence that names them)."""
+    w, _, _ = host_model(SHAPE, seed)
+    cfg = oracle.make_config(SHAPE)
+    okv = oracle.PagedKV(cfg, n_blocks)
+    for l, (k, v) in enumerate(data):
+        okv.fill(l, synth.as_u16(k), synth.as_u16(v), start, table)
+    ctx = np.asarray(ctx, dtype=np.int32)
+    return oracle.decode_step(cfg, w, okv, np.asarray(tokens, np.int32), ctx, ctx + 1, table, want_attn=True)
+
+
+def check_against_oracle(gpu, ref, what):
+    (gl, gt, ga), (rl, rt, ra) = gpu, ref
+    rep = compare_step(gl.numpy(), gt.numpy(), ga.numpy(), rl, rt, ra, what)
+    assert rep.agreement == 1.0 or all(d <= b for _, d, b in rep.mismatches)
 
 
 def test_response_groups_share_the_blocks_of_their_prompt(hx):
@@ -96,7 +122,9 @@ def test_response_groups_share_the_blocks_of_their_prompt(hx):
         kv.pool.zero_()
         for l, (k, v) in enumerate(data):
             kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table))
-        outs.append(step(eng, kv, tokens, ctx, table))
+        outs.append(step(eng, kv, tokens, ctx, table, want_attn=True))
+        # the oracle over its own cache, filled through the same (private or shared-prefix) table
+        check_against_oracle(outs[-1], oracle_step(7, data, start, table, n, tokens, ctx), "shared prefix, %d blocks" % n)
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
     assert torch.isfinite(outs[0][0]).all()
 
@@ -120,14 +148,19 @@ def test_sequences_leave_and_join_between_steps(hx):
     start = np.concatenate([[0], np.cumsum(ctx_all)]).astype(np.int32)
     kv = hx.KVCache(eng, n)
     kv.pool.zero_()
-    for l in range(SHAPE.n_layers):
-        k, v = synth.kv_fill(SHAPE, l, int(ctx_all.sum()), 99)
+    data = [synth.kv_fill(SHAPE, l, int(ctx_all.sum()), 99) for l in range(SHAPE.n_layers)]
+    for l, (k, v) in enumerate(data):
         kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table_all))
     tokens_all = rng.integers(0, SHAPE.vocab, size=7)
 
-    def run(rows):
+    def run(rows, want_attn=False):
         rows = list(rows)
-        return step(eng, kv, tokens_all[rows], ctx_all[rows], table_all[rows])
+        return step(eng, kv, tokens_all[rows], ctx_all[rows], table_all[rows], want_attn)
+
+    # the oracle steps all seven sequences once (rows are independent): every batch composition is compared with it
+    rl, rt, ra = oracle_step(8, data, start, table_all, n, tokens_all, ctx_all)
+    for rows in (list(range(6)), [0, 2, 3, 5, 6], [6]):
+        check_against_oracle(run(rows, want_attn=True), (rl[rows], rt[rows], ra[:, rows]), "batch of rows %s" % rows)
 
     alone = [run([b]) for b in range(7)]        # each step re-writes the same K/V at position ctx: idempotent
     first = run(range(6))
@@ -150,11 +183,12 @@ def test_new_policy_version_packed_into_a_live_engine(hx):
     start = np.concatenate([[0], np.cumsum(ctx)]).astype(np.int32)
     tokens = rng.integers(0, SHAPE.vocab, size=3)
 
+    data = [synth.kv_fill(SHAPE, l, int(ctx.sum()), 5) for l in range(SHAPE.n_layers)]
+
     def cache_for(eng):
         kv = hx.KVCache(eng, n)
         kv.pool.zero_()
-        for l in range(SHAPE.n_layers):
-            k, v = synth.kv_fill(SHAPE, l, int(ctx.sum()), 5)
+        for l, (k, v) in enumerate(data):
             kv.prefill_fill(l, k.cuda(), v.cuda(), dev(start), dev(table))
         return kv
 
@@ -170,11 +204,17 @@ def test_new_policy_version_packed_into_a_live_engine(hx):
     out_b = step(fresh_b, cache_for(fresh_b), tokens, ctx, table)
     assert not torch.equal(out_a[0], out_b[0])
     pack(live, 22)
-    swapped = step(live, cache_for(live), tokens, ctx, table)
+    swapped = step(live, cache_for(live), tokens, ctx, table, want_attn=True)
     assert torch.equal(swapped[0], out_b[0]) and torch.equal(swapped[1], out_b[1])
+    # ... and it computes what the oracle computes with version B's weights (and no longer what it computes with A's)
+    ref_b = oracle_step(22, data, start, table, n, tokens, ctx)
+    check_against_oracle(swapped, ref_b, "live engine after packing version B")
+    ref_a = oracle_step(21, data, start, table, n, tokens, ctx)
+    assert float(np.abs(swapped[0].numpy() - ref_a[0]).max()) > 0.1 * float(np.abs(ref_a[0]).max())
     pack(live, 21)
-    back = step(live, cache_for(live), tokens, ctx, table)
+    back = step(live, cache_for(live), tokens, ctx, table, want_attn=True)
     assert torch.equal(back[0], out_a[0])
+    check_against_oracle(back, ref_a, "live engine after packing version A again")
 
 
 def test_device_side_inputs_are_validated_without_running_the_step(hx):

@@ -1,15 +1,13 @@
-"""Checks the CPU pins of the oracle by mutation: plants ONE mistake at a time in a scratch copy of
+"""The CPU pins of the oracle, checked by mutation: ONE mistake at a time is planted in a scratch copy of
 oracle/decode_oracle.c (a dropped term, a wrong sign or index, a transposed operand, a rounding mode, a generator
-constant, a tie rule ...), rebuilds it there and runs the `-m "not gpu"` oracle tests, which must fail.  CPU only; the
-repository itself is not modified.  Not collected by pytest; run it by hand after changing the oracle or its pins:
+constant, a tie rule ...), the copy is rebuilt and the oracle's pins (tests/test_oracle_*.py) are run against it in a
+child process: every planted mistake must make at least one pin fail.  CPU only; the repository is not modified.
 
-    python tests/oracle_mutation_check.py [substring of a mutation's name]
-
-Exit status 0 iff every planted mistake is caught.
+    python tests/test_oracle_mutations.py [substring of a mutation's name]     # by hand, verbose
 """
 import os, shutil, subprocess, sys, tempfile
+from concurrent.futures import ThreadPoolExecutor
 SRC = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-DST = os.path.join(tempfile.gettempdir(), "oracle_mutation_check")
 MUT = [
  ("rmsnorm: sum instead of mean", "float r = 1.0f / sqrtf(ss / (float)n + eps);", "float r = 1.0f / sqrtf(ss + eps);"),
  ("rmsnorm: gain dropped", "y[i] = x[i] * r * orc_bf16_to_f32(g[i]);", "y[i] = x[i] * r;"),
@@ -43,35 +41,64 @@ MUT = [
  ("top-p: strict comparison at the cut", "if (cum >= (double)top_p) break;", "if (cum > (double)top_p + 1e-3) break;"),
  ("top-p: ties with the last kept entry dropped", "while (n < V && ord[n].z == ord[n - 1].z) ++n;", ";"),
  ("top-p: logprob under the full distribution", "*logprob = (float)((double)(logits[best_i] * inv_t) - ((double)zmax + log(mass)));", "*logprob = (float)((double)(logits[best_i] * inv_t) - ((double)zmax + log(sum)));"),
- ("full causal: future key visible", "for (int r = 0; r <= t; ++r) { /* causal mask: keys 0..t only */\n                    float dot = 0.0f;\n                    for (int j = 0; j < d; ++j)\n                        dot += Q[(size_t)t * QD + h * d + j] * Km[(size_t)r * KD + kvh * d + j];\n                    s[r] = dot * scale;\n                }\n                orc_softmax(s, t + 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                for (int r = 0; r <= t; ++r)", "const int t2 = t + 1 < n ? t + 1 : t;\n                for (int r = 0; r <= t2; ++r) {\n                    float dot = 0.0f;\n                    for (int j = 0; j < d; ++j)\n                        dot += Q[(size_t)t * QD + h * d + j] * Km[(size_t)r * KD + kvh * d + j];\n                    s[r] = dot * scale;\n                }\n                orc_softmax(s, t2 + 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                for (int r = 0; r <= t2; ++r)"),
+ ("full causal: future key visible", "for (int r = 0; r <= t; ++r) { /* causal mask: keys 0..t only */\n                    float dot = 0.0f;\n                    ORC_FOR_SUM(j, d)\n                        dot += Q[(size_t)t * QD + h * d + j] * Km[(size_t)r * KD + kvh * d + j];\n                    s[r] = dot * scale;\n                }\n                orc_softmax(s, t + 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                ORC_FOR_SUM(r, t + 1)", "const int t2 = t + 1 < n ? t + 1 : t;\n                for (int r = 0; r <= t2; ++r) {\n                    float dot = 0.0f;\n                    ORC_FOR_SUM(j, d)\n                        dot += Q[(size_t)t * QD + h * d + j] * Km[(size_t)r * KD + kvh * d + j];\n                    s[r] = dot * scale;\n                }\n                orc_softmax(s, t2 + 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                ORC_FOR_SUM(r, t2 + 1)"),
+ ("full causal: last key not attended", "orc_softmax(s, t + 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                ORC_FOR_SUM(r, t + 1)", "orc_softmax(s, t > 0 ? t : 1, p);\n                for (int j = 0; j < d; ++j) o[h * d + j] = 0.0f;\n                ORC_FOR_SUM(r, t > 0 ? t : 1)"),
 ]
-def run():
-    shutil.rmtree(DST, ignore_errors=True)
-    os.makedirs(DST)
-    ignore = shutil.ignore_patterns("*.so", "__pycache__", "_build", "*.o")
-    for d in ("oracle", "tests", "paper_2511_00796_amd", "include"):
-        shutil.copytree(os.path.join(SRC, d), os.path.join(DST, d), ignore=ignore)
-    src = open(DST + "/oracle/decode_oracle.c").read()
-    res = []
-    for name, old, new in (MUT if len(sys.argv) < 2 else [m for m in MUT if sys.argv[1] in m[0]]):
-        n = src.count(old)
-        if n != 1 and not name.startswith("bf16"):
-            res.append((name, "PATTERN matches %d times" % n)); print(res[-1], flush=True); continue
-        open(DST + "/oracle/decode_oracle.c", "w").write(src.replace(old, new, 1))
-        for f in ("liboracle.so", "liboracle_desc.so"):
-            try: os.remove(DST + "/oracle/" + f)
-            except OSError: pass
-        r = subprocess.run([sys.executable, "-m", "pytest", "tests", "-x", "-q", "-m", "not gpu", "-k", "oracle", "-p", "no:cacheprovider"],
-                           cwd=DST, capture_output=True, text=True, timeout=900)
-        tail = [l for l in r.stdout.splitlines() if "FAILED" in l or "passed" in l or "failed" in l or "error" in l.lower()]
-        verdict = "caught" if r.returncode != 0 else "NOT CAUGHT"
-        first = next((l for l in tail if "FAILED" in l), tail[-1] if tail else "")
-        res.append((name, verdict, first[:110])); print(res[-1], flush=True)
-    open(DST + "/oracle/decode_oracle.c", "w").write(src)
-    caught = sum(1 for r in res if r[1] == "caught")
-    print("caught %d of %d" % (caught, len(res)))
-    return 0 if caught == len(res) else 1
+CONTROL = ("control: the unchanged oracle passes its pins", None, None)
+
+
+def mutant_verdict(item):
+    """Plant one mistake in a scratch copy of its own, rebuild, run the pins; -> (name, verdict, first failing test)."""
+    idx, (name, old, new) = item
+    dst = tempfile.mkdtemp(prefix="oracle_mutant_%02d_" % idx)
+    try:
+        shutil.copytree(os.path.join(SRC, "oracle"), os.path.join(dst, "oracle"), ignore=shutil.ignore_patterns("*.so", "__pycache__"))
+        # of the tests only the oracle's pins and what they import
+        shutil.copytree(os.path.join(SRC, "tests"), os.path.join(dst, "tests"),
+                        ignore=lambda d, names: [n for n in names if not (n.startswith("test_oracle_") or n in ("util.py", "conftest.py", "golden")
+                                                                          or d.endswith("golden")) or n == "test_oracle_mutations.py"])
+        os.makedirs(os.path.join(dst, "paper_2511_00796_amd"))
+        for f in ("__init__.py", "synth.py"):
+            shutil.copy(os.path.join(SRC, "paper_2511_00796_amd", f), os.path.join(dst, "paper_2511_00796_amd", f))
+        path = os.path.join(dst, "oracle", "decode_oracle.c")
+        src = open(path).read()
+        if old is not None:
+            n = src.count(old)
+            if n != 1 and not name.startswith("bf16"):
+                return name, "PATTERN matches %d times" % n, ""
+            open(path, "w").write(src.replace(old, new, 1))
+        env = dict(os.environ, OMP_NUM_THREADS="2")
+        r = subprocess.run([sys.executable, "-m", "pytest", "tests", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"], cwd=dst, capture_output=True, text=True, timeout=900, env=env)
+        lines = [l for l in r.stdout.splitlines() if "FAILED" in l or "passed" in l or "failed" in l or "error" in l.lower()]
+        first = next((l for l in lines if "FAILED" in l), lines[-1] if lines else "")
+        failed = r.returncode == 1 and " failed" in r.stdout and " error" not in r.stdout.splitlines()[-1]
+        return name, "caught" if failed else ("NOT CAUGHT" if r.returncode == 0 else "rc=%d: %s" % (r.returncode, r.stdout[-300:])), first[:110]
+    finally:
+        shutil.rmtree(dst, ignore_errors=True)
+
+
+def run(select=None, workers=None, verbose=False):
+    todo = [CONTROL] + [m for m in MUT if select is None or select in m[0]]
+    workers = workers or max(1, min(8, (os.cpu_count() or 2) // 2))
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        res = []
+        for r in pool.map(mutant_verdict, enumerate(todo)):
+            res.append(r)
+            if verbose:
+                print(r, flush=True)
+    return res
+
+
+def test_every_planted_mistake_in_the_oracle_fails_a_pin():
+    res = run()
+    assert res[0][1] == "NOT CAUGHT", res[0]             # the scratch copy works: the unchanged oracle passes
+    missed = [r for r in res[1:] if r[1] != "caught"]
+    print("caught %d of %d planted mistakes" % (len(res) - 1 - len(missed), len(res) - 1))
+    assert len(res) - 1 == len(MUT) >= 34
+    assert not missed, missed
 
 
 if __name__ == "__main__":
-    sys.exit(run())
+    out = run(sys.argv[1] if len(sys.argv) > 1 else None, verbose=True)
+    print("caught %d of %d" % (sum(1 for r in out[1:] if r[1] == "caught"), len(out) - 1))
+    sys.exit(0 if out[0][1] == "NOT CAUGHT" and all(r[1] == "caught" for r in out[1:]) else 1)

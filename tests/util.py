@@ -34,10 +34,13 @@ class OracleRows:
     paper_2511_00796_amd.workload.build).  Rows are independent in the decode step, so the sampled
     rows' results are exactly what the full-batch oracle would give for them."""
 
-    def __init__(self, shape, rows, ctx, seq_start, tokens, descending=False, kv_fp8=False):
+    def __init__(self, shape, rows, ctx, seq_start, tokens, descending=False, kv_fp8=False, keep_layers=()):
         from concurrent.futures import ThreadPoolExecutor
         self.shape, self.rows = shape, list(rows)
-        self.descending = descending          # run the equally valid descending-k variant of the oracle
+        self.descending = descending          # run the equally valid variant of the oracle with every sum reversed
+        self.keep_layers = set(keep_layers)   # layers whose residual stream before / after, intermediate results and
+        self.x_before, self.x_after = {}, {}  # product magnitudes sum_k |x_k w_kn| are kept per row
+        self.trace, self.mag, self.layer_bias = {}, {}, {}
         self.ctx, self.seq_start, self.tokens = ctx, seq_start, tokens
         self.cfg1 = oracle.make_config(shape, kv_fp8=kv_fp8)   # kv_fp8: the 8-bit cache variant
         self.cfg1.n_layers = 1
@@ -74,10 +77,27 @@ class OracleRows:
                 k = synth.as_u16(t["k"][a:a + c])
                 v = synth.as_u16(t["v"][a:a + c])
                 kv.fill(0, k, v, np.array([0, c], dtype=np.int32), table)
-                att = oracle.layer_step(self.cfg1, w1.layer(0), self.x[r], c, kv.k[0], kv.v[0], table[0], want_attn=True)
+                tr = {} if layer in self.keep_layers else None
+                att = oracle.layer_step(self.cfg1, w1.layer(0), self.x[r], c, kv.k[0], kv.v[0], table[0], want_attn=True, trace=tr)
+                if tr is not None:
+                    self.trace[layer][r] = tr
                 return r, att
+            if layer in self.keep_layers:
+                self.x_before[layer] = {r: self.x[r].copy() for r in self.rows}
+                self.trace[layer] = {}
+                self.layer_bias[layer] = self.layer_w["bqkv"].copy()
             for r, att in self.pool.map(run, self.rows):
                 self.attn[r].append(att)
+            if layer in self.keep_layers:
+                self.x_after[layer] = {r: self.x[r].copy() for r in self.rows}
+                # sum_k |x_k| |w_kn| of every product of the layer, per kept row: the scale of its fp32 rounding error
+                tr = self.trace[layer]
+
+                def mags(inp, *names):
+                    xa = np.abs(np.stack([bits_to_f32(f32_to_bf16_bits_ref(tr[r][inp])) for r in self.rows]))
+                    return [dict(zip(self.rows, xa @ np.abs(bits_to_f32(self.layer_w[n])))) for n in names]
+                self.mag[layer] = dict(zip(("qkv", "o", "g", "u", "d"),
+                                           mags("u1", "wqkv") + mags("o", "wo") + mags("u2", "wg", "wu") + mags("m", "wd")))
 
     def finish(self):
         if self.descending:
