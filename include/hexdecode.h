@@ -245,9 +245,7 @@ int hx_set_attn_capture(hx_engine *engine, float *attn_dev);
 /* Schedule of the split-K attention.  A tile is the K and V of 16 tokens of one KV head; the tiles of the batch,
    in (sequence, KV head, block) order, are cut into hx_attention_waves(engine) equal runs, one per wavefront.
    Outputs are DEVICE int32: prefix_out [batch + 1] = exclusive prefix sum of ceil(seq_lens[b] / 16);
-   sched_out [2] = { tiles per run, total tiles = prefix_out[batch] * n_kv_heads }; tiles per run =
-   ceil(total / waves), except that batches of 8192 to 44999 tiles are cut into 1024 runs (ceil(total / 1024)) when
-   there are more than 1024 wavefronts: fewer, longer runs are faster there. */
+   sched_out [2] = { tiles per run = ceil(total / waves), total tiles = prefix_out[batch] * n_kv_heads }. */
 int hx_stage_schedule(hx_engine *engine, int32_t batch, const int32_t *seq_lens, int32_t *prefix_out,
                       int32_t *sched_out, void *stream);
 int hx_attention_waves(const hx_engine *engine); /* wavefronts of the attention kernel */

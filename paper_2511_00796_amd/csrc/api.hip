@@ -138,6 +138,7 @@ static size_t map_workspace(hx_engine *e) {
     m->pre = take(HX_PREFIX_LEN * 4);
     m->lens = take(256 * 4);
     m->sched = take(256);
+    m->blk_new = take(256 * 4);
     const size_t slots = (size_t)e->attn_waves + B * c->n_kv_heads;
     m->part_ml = take(slots * 32 * 4);
     m->part_o = take(slots * e->G * e->D * 4);
@@ -432,7 +433,7 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
     float *ypart = (float *)(ws + e->map.ypart);
     const size_t attn_stride = (size_t)batch * e->q_dim;
 
-    HX_TIMED(HX_K_SETUP, hx_launch_step_setup(e, batch, positions, seq_lens, st));
+    HX_TIMED(HX_K_SETUP, hx_launch_step_setup(e, batch, positions, seq_lens, block_table, max_blocks, st));
     // prompt rows: consecutive rows of a sequence share one K/V stream (their schedule replaces the decode step's)
     const bool chunked = !with_head && e->chunk_attention;
     if (chunked) HX_TIMED(HX_K_SETUP, hx_launch_chunk_setup(e, batch, seq_lens, block_table, max_blocks, st));
@@ -441,7 +442,7 @@ static int run_step(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *token
         const hx_layer_map *lm = &e->layers[l];
         HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm(e, &lm->wqkv, batch, ws + e->map.xp, HX_EPI_PARTIAL, ypart, nullptr, st));
         HX_TIMED(HX_K_ROPE, hx_launch_rope_append(e, kv, l, batch, ypart, hx_gemm_splits(&lm->wqkv, batch), (size_t)batch * e->qkv_dim,
-                                                 positions, block_table, max_blocks, st));
+                                                 positions, st));
         if (!with_head && l + 1 == c->n_layers) break;   // prompt rows: of the last layer only its K and V are needed
         float *capture = e->attn_capture ? e->attn_capture + l * attn_stride : nullptr;
         if (chunked) {
@@ -593,7 +594,7 @@ extern "C" int hx_stage_schedule(hx_engine *e, int32_t batch, const int32_t *seq
     if (rc) return rc;
     if (!seq_lens || !prefix_out || !sched_out) return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
+    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, nullptr, 0, st))) return rc;
     HX_CHECK_HIP(hipMemcpyAsync(prefix_out, e->ws + e->map.pre, ((size_t)batch + 1) * 4, hipMemcpyDeviceToDevice, st));
     HX_CHECK_HIP(hipMemcpyAsync(sched_out, e->ws + e->map.sched, 8, hipMemcpyDeviceToDevice, st));
     return HX_OK;
@@ -607,8 +608,8 @@ extern "C" int hx_stage_rope_append(hx_engine *e, hx_kv *kv, int layer, int32_t 
     if (!kv || !qkv_dev || !positions || !block_table || !q_out_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
     if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = hx_launch_step_setup(e, batch, positions, nullptr, st))) return rc;
-    if ((rc = hx_launch_rope_append(e, kv, layer, batch, qkv_dev, 1, 0, positions, block_table, max_blocks, st))) return rc;
+    if ((rc = hx_launch_step_setup(e, batch, positions, nullptr, block_table, max_blocks, st))) return rc;
+    if ((rc = hx_launch_rope_append(e, kv, layer, batch, qkv_dev, 1, 0, positions, st))) return rc;
     return hx_launch_unpack_q(e, batch, q_out_dev, st);
 }
 
@@ -621,7 +622,7 @@ extern "C" int hx_stage_attention(hx_engine *e, hx_kv *kv, int layer, int32_t ba
     if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hx_launch_pack_q(e, batch, q_dev, st))) return rc;
-    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, st))) return rc;
+    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, nullptr, 0, st))) return rc;
     if (kv->fp8) rc = hx_launch_attention_fp8(e, kv, layer, block_table, max_blocks, st);
     else rc = hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, st);
     if (rc) return rc;

@@ -4,7 +4,7 @@
 //
 // Work decomposition ("stream-K").  A tile is the K and V of 16 tokens of one KV head.  All tiles of the
 // batch are lined up in (sequence, KV head, block) order and cut into W equal runs of S = ceil(Nt / W)
-// tiles, one run per wavefront, W = 8 per compute unit (smallish batches: 1024 runs, see step_setup_kernel).
+// tiles, one run per wavefront, W = 8 per compute unit.
 // Every wavefront therefore streams the same
 // number of bytes whatever the length mix, all of them are resident at once and finish together, and a
 // run is long (about 1 MiB at the 7B shape), so start-up latency is paid once.  A run that crosses from
@@ -26,13 +26,15 @@
 // ---- per-step setup: schedule + RoPE angles ----------------------------------------------------------------
 // block 0: sched[0] = S (tiles per wavefront), sched[1] = Nt (tiles in all), pre[b] = blocks of the sequences
 // before b (pre[b] = total for b >= batch, HX_PREFIX_LEN entries), lens[b] = seq_lens[b] (0 for b >= batch).
-// blocks 1..batch: cos/sin of pos * theta^(-2i/D), evaluated in double, stored fp32.
+// blocks 1..batch: cos/sin of pos * theta^(-2i/D), evaluated in double, stored fp32; and the physical block that
+// holds the new position (one look-up per step instead of one per layer in the append kernel).
 __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, int n_waves,
                                                          const int32_t *__restrict__ positions,
                                                          const int32_t *__restrict__ seq_lens,
+                                                         const int32_t *__restrict__ table, int max_blocks,
                                                          int32_t *__restrict__ pre, int32_t *__restrict__ lens,
-                                                         int32_t *__restrict__ sched, float *__restrict__ cs, int half,
-                                                         double theta, int max_batch) {
+                                                         int32_t *__restrict__ sched, int32_t *__restrict__ blk_new,
+                                                         float *__restrict__ cs, int half, double theta, int max_batch) {
     if (blockIdx.x == 0) {
         if (seq_lens == nullptr) return;
         __shared__ int32_t scan[256];
@@ -52,19 +54,13 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, in
         lens[b] = T;
         for (int i = 256 + b; i < HX_PREFIX_LEN; i += 256) pre[i] = total;
         if (b == 0) {
-            // A run costs its wavefront a schedule look-up, a query load and a partial result (and the combine one
-            // more term per pair), so a smallish batch is cut into 1024 runs (4 per compute unit) instead of one per
-            // wavefront; the other wavefronts exit at once.  Measured at the 1.5B shape (2 KV heads), tiles -> us per
-            // attention launch with 2048 / 1024 runs: 17k 35.0 / 34.5, 35k 56.3 / 54.8, 51k 75.8 / 75.8, 74k 104.8 /
-            // 108.1, 137k 185 / 192 (and the combine 9.7 / 7.5 us); a run count that is not a multiple of the 256
-            // compute units (1088 runs of 32 tiles) was slower than either (61.7 us at 35k).
             const long long nt = (long long)total * n_kv;
-            const long long s_even = (nt + n_waves - 1) / n_waves, s_1024 = (nt + 1023) / 1024;
-            sched[0] = (int)((nt >= 8192 && nt < 45000 && n_waves > 1024) ? s_1024 : s_even);
+            sched[0] = (int)((nt + n_waves - 1) / n_waves);
             sched[1] = (int)nt;
         }
     } else if (positions != nullptr) {
         int b = blockIdx.x - 1;
+        if (threadIdx.x == 0 && table != nullptr) blk_new[b] = table[(size_t)b * max_blocks + (positions[b] >> 4)];
         double pos = (double)positions[b];
         for (int i = threadIdx.x; i < half; i += blockDim.x) {
             double ang = pos * pow(theta, -(double)i / (double)half);
@@ -75,12 +71,12 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, in
 }
 
 int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
-                         hipStream_t st) {
+                         const int32_t *table, int max_blocks, hipStream_t st) {
     char *ws = e->ws;
     hipLaunchKernelGGL(step_setup_kernel, dim3(batch + 1), dim3(256), 0, st, batch, e->cfg.n_kv_heads, e->attn_waves,
-                       positions, seq_lens, (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
-                       (int32_t *)(ws + e->map.sched), (float *)(ws + e->map.cs), e->D / 2, (double)e->cfg.rope_theta,
-                       e->cfg.max_batch);
+                       positions, seq_lens, table, max_blocks, (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
+                       (int32_t *)(ws + e->map.sched), (int32_t *)(ws + e->map.blk_new), (float *)(ws + e->map.cs), e->D / 2,
+                       (double)e->cfg.rope_theta, e->cfg.max_batch);
     HX_CHECK_LAUNCH("step_setup");
     return HX_OK;
 }

@@ -83,13 +83,20 @@ __global__ __launch_bounds__(HX_NORM_THREADS) void norm_kernel(float *__restrict
             for (int j = 0; j < 8; ++j) ss += v[it][j] * v[it][j];
         }
     }
+    // the gains are requested before the block-wide sum, so their round trip overlaps it
+    uint4 graw_all[HX_NORM_MAX_IT];
+#pragma unroll
+    for (int it = 0; it < HX_NORM_MAX_IT; ++it) {
+        const int i0 = (it * HX_NORM_THREADS + threadIdx.x) * 8;
+        graw_all[it] = i0 < H ? *(const uint4 *)(gain + i0) : make_uint4(0u, 0u, 0u, 0u);
+    }
     ss = block_sum(ss, red);
     const float r = 1.0f / sqrtf(ss / (float)H + eps);
 #pragma unroll
     for (int it = 0; it < HX_NORM_MAX_IT; ++it) {
         const int i0 = (it * HX_NORM_THREADS + threadIdx.x) * 8;
         if (i0 < H) {
-            const uint4 graw = *(const uint4 *)(gain + i0);
+            const uint4 graw = graw_all[it];
             const uint16_t *g16 = (const uint16_t *)&graw;
             float u[8];
 #pragma unroll

@@ -184,6 +184,7 @@ struct hx_ws_map {          // byte offsets in the workspace
     size_t qp;              // bf16 packed queries [max_batch][n_kv][D/32][64][8]
     size_t cs;              // fp32 [max_batch][D/2] cos, then [max_batch][D/2] sin
     size_t pre, lens, sched;  // int32 attention schedule: block prefix [HX_PREFIX_LEN], lengths [256], {S, Nt}
+    size_t blk_new;         // int32 [256] physical block of each sequence's new position (per step)
     size_t part_ml;         // fp32 [slots][32]     running max (16) | sum (16); slots = attn_waves + max_batch*n_kv
     size_t part_o;          // fp32 [slots][G][D]   unnormalised partial outputs
     // prompt chunks (attention_chunk.hip): rows grouped by sequence, partial results of 4 column blocks per slot
@@ -236,12 +237,11 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
                          const int32_t *table, int max_blocks, int batch, int64_t total_tokens, bool gather,
                          hipStream_t st);
 int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int batch, const float *ypart,
-                          int splits, size_t split_stride, const int32_t *positions, const int32_t *table,
-                          int max_blocks, hipStream_t st);
+                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st);
 
 // attention.hip
 int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
-                         hipStream_t st);
+                         const int32_t *table, int max_blocks, hipStream_t st);   // table may be NULL when positions is
 int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
                         const int32_t *table, int max_blocks, hipStream_t st);
 int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st);

@@ -109,7 +109,7 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
 // split order), the bias is added, q and k heads are rotated by the position's angles (pairs (i, i + D/2)),
 // q is written as the packed bf16 B operand of the attention kernel, k and v are rounded to bf16 (or, for an 8-bit
 // cache, from fp32 straight to E4M3) and stored
-// at (block_table[b][pos/16], pos%16).
+// at (block_table[b][pos/16], pos%16); the block id comes from the per-step table written by step_setup_kernel.
 // One thread per work item of 16 values: for q and k heads, 8 consecutive d of the lower half and the 8
 // matching d of the upper half (both ends of the rotation, two 16-byte stores); for v, 16 consecutive d.
 // grid (batch, ceil(items / 128)), 128 threads.  Query rows g >= G of the packed operand are never written:
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
                                                           size_t split_stride, const uint16_t *__restrict__ bias,
                                                           int has_bias, const float *__restrict__ cs,
                                                           const int32_t *__restrict__ positions,
-                                                          const int32_t *__restrict__ table, int max_blocks,
+                                                          const int32_t *__restrict__ blk_new,
                                                           char *pool_layer, size_t block_bytes, size_t tile_bytes,
                                                           uint16_t *__restrict__ qp, int n_q, int n_kv, int G,
                                                           int max_batch) {
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
     if (item >= rot_items + v_items) return;
     const int qkv_dim = (n_q + 2 * n_kv) * D;
     const int pos = positions[b];
-    const int32_t blk = table[(size_t)b * max_blocks + (pos >> 4)];
+    const int32_t blk = blk_new[b];                     // block of position pos, looked up once per step
     const int slot = pos & 15;
 
     auto gather8 = [&](int col, float *out) {            // sum of the split partials + bias, 8 consecutive columns
@@ -219,8 +219,7 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
 }
 
 int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int batch, const float *ypart,
-                          int splits, size_t split_stride, const int32_t *positions, const int32_t *table,
-                          int max_blocks, hipStream_t st) {
+                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st) {
     const hx_layer_map &lm = e->layers[layer];
     char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     const uint16_t *bias = (const uint16_t *)(e->weights + lm.bqkv);
@@ -230,7 +229,7 @@ int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int ba
     dim3 grid(batch, (items + 127) / 128), block(128);
 #define HX_ROPE_LAUNCH(DD, F8)                                                                                  \
     hipLaunchKernelGGL((rope_append_kernel<DD, F8>), grid, block, 0, st, ypart, splits, split_stride, bias,    \
-                       e->cfg.qkv_bias, cs, positions, table, max_blocks, pool_layer, kv->block_bytes,         \
+                       e->cfg.qkv_bias, cs, positions, (const int32_t *)(e->ws + e->map.blk_new), pool_layer, kv->block_bytes, \
                        kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch)
     if (e->D == 128) { if (kv->fp8) HX_ROPE_LAUNCH(128, true); else HX_ROPE_LAUNCH(128, false); }
     else             { if (kv->fp8) HX_ROPE_LAUNCH(64, true);  else HX_ROPE_LAUNCH(64, false); }
