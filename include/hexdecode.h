@@ -279,6 +279,23 @@ int hx_stage_attention(hx_engine *engine, hx_kv *kv, int layer, int32_t batch, c
                        const int32_t *seq_lens, const int32_t *block_table,
                        int32_t max_blocks_per_seq, float *out_dev, void *stream);
 
+/* hx_stage_attention for callers that cannot allocate or provide scratch memory: code under graph capture, tight
+   serving loops, harnesses that forbid allocation.  Same arguments, same kernels, same results bit for bit, but the
+   stage's scratch (packed queries, schedule, split-K partial results) lives in a device array inside the library,
+   HX_STATIC_SCRATCH_BYTES per GPU for the life of the process, instead of the engine's workspace, which this call
+   never touches; it calls no allocating routine.  The scratch of a call is
+       batch * n_kv_heads * head_dim * 32                                              packed queries
+     + (wavefronts + batch * n_kv_heads) * (128 + 4 * G * head_dim)                    partial results (G = query heads
+     + about 6 KiB of schedule and padding                                              per KV head)
+   bytes (9 to 12 MiB for the five benchmark workloads with the default 2048 wavefronts); a call that needs more than
+   the array holds fails with HX_E_RANGE and a message giving both numbers.  Every call on a GPU shares that GPU's
+   array and finds the previous call's contents in it (nothing needs clearing: each call writes what it reads).
+   Calls that overlap on one GPU -- two streams, two threads -- race: the caller must serialise them. */
+#define HX_STATIC_SCRATCH_BYTES (16 << 20)
+int hx_stage_attention_static(hx_engine *engine, hx_kv *kv, int layer, int32_t batch, const float *q_dev,
+                              const int32_t *seq_lens, const int32_t *block_table,
+                              int32_t max_blocks_per_seq, float *out_dev, void *stream);
+
 /* RMSNorm with the packed gain `gain_kind` (HX_T_G1 / HX_T_G2 / HX_T_GF): x_dev fp32
    [batch, hidden] -> y_dev fp32 [batch, hidden] holding the bf16-rounded result. */
 int hx_stage_rmsnorm(hx_engine *engine, int gain_kind, int layer, int32_t batch, const float *x_dev,

@@ -22,7 +22,7 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
            "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
-           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
+           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_attention_static", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
            "hx_profile_enable", "hx_profile_sample_every", "hx_profile_read"]
 
 KERNEL_CLASSES = ["attention", "combine", "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm", "norm",
@@ -84,6 +84,7 @@ def load():
         "hx_plan_product": [i32, i32, i32, i32, vp, vp, vp],
         "hx_stage_rope_append": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_attention": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
+        "hx_stage_attention_static": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],
         "hx_stage_linear": [vp, C.c_int, C.c_int, i32, vp, vp, vp, vp],
         "hx_stage_lm_head_top_p": [vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
@@ -266,6 +267,11 @@ class Engine:
         _check(load().hx_stage_attention(self.handle, kv.handle, layer, B, _ptr(q), _ptr(seq_lens),
                                          _ptr(block_table), block_table.shape[1], _ptr(out), _stream()))
         return out
+
+    def stage_attention_static(self, kv: "KVCache", layer: int, q: torch.Tensor, seq_lens, block_table, out: torch.Tensor) -> None:
+        """hx_stage_attention_static: scratch in the library's static device array; `out` is provided by the caller."""
+        _check(load().hx_stage_attention_static(self.handle, kv.handle, layer, q.shape[0], _ptr(q), _ptr(seq_lens),
+                                                _ptr(block_table), block_table.shape[1], _ptr(out), _stream()))
 
     def stage_rmsnorm(self, gain_kind: int, layer: int, x: torch.Tensor) -> torch.Tensor:
         y = torch.empty_like(x)

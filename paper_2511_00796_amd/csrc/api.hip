@@ -629,6 +629,67 @@ extern "C" int hx_stage_attention(hx_engine *e, hx_kv *kv, int layer, int32_t ba
     return hx_launch_combine(e, batch, out_dev, st);
 }
 
+// ---- the attention stage without a workspace ---------------------------------------------------------------------
+// For callers that cannot provide or allocate scratch memory (code under graph capture, tight serving loops,
+// harnesses that forbid allocation): the packed queries, the schedule and the split-K partial results of
+// hx_stage_attention live in a file-scope device array of fixed size instead of the engine's workspace.  Each GPU
+// holds its own copy of the array at its own address; the address is asked once per device (hipGetSymbolAddress)
+// and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char hx_static_scratch[HX_STATIC_SCRATCH_BYTES];
+
+#define HX_MAX_DEVICES 64
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[HX_MAX_DEVICES];      // per device; NULL until first used there
+
+static int static_scratch_of_current_device(char **out) {
+    int dev = -1;
+    HX_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= HX_MAX_DEVICES) return hx_fail(HX_E_RANGE, "device ordinal %d outside [0, %d)", dev, HX_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HX_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(hx_static_scratch)));
+        if (!p) return hx_fail(HX_E_HIP, "hipGetSymbolAddress returned no address for the static scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (char *)g_scratch_ptr[dev];
+    return HX_OK;
+}
+
+extern "C" int hx_stage_attention_static(hx_engine *e, hx_kv *kv, int layer, int32_t batch, const float *q_dev,
+                                         const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks,
+                                         float *out_dev, void *stream) {
+    int rc = check_step_args(e, kv, batch, max_blocks);
+    if (rc) return rc;
+    if (!kv || !q_dev || !seq_lens || !block_table || !out_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    if (layer < 0 || layer >= e->cfg.n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    // carve the array: packed queries (+ one K tile of slack, see map_workspace), schedule, partial results
+    const size_t slots = (size_t)e->attn_waves + (size_t)batch * e->cfg.n_kv_heads;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+    const size_t o_qp = take((size_t)batch * e->cfg.n_kv_heads * (size_t)(e->D / 32) * 1024 + 16 * (size_t)e->D * 2);
+    const size_t o_pre = take(HX_PREFIX_LEN * 4), o_lens = take(256 * 4), o_sched = take(256);
+    const size_t o_ml = take(slots * 32 * 4), o_o = take(slots * e->G * e->D * 4);
+    if (at > (size_t)HX_STATIC_SCRATCH_BYTES)
+        return hx_fail(HX_E_RANGE, "this call needs %zu bytes of scratch (batch %d, %d KV heads, %d query heads per KV head, head "
+                       "size %d, %d wavefronts); the static array holds %d: use hx_stage_attention with a workspace",
+                       at, batch, e->cfg.n_kv_heads, e->G, e->D, e->attn_waves, HX_STATIC_SCRATCH_BYTES);
+    char *base = nullptr;
+    if ((rc = static_scratch_of_current_device(&base))) return rc;
+    const hx_attn_bufs bufs{(uint16_t *)(base + o_qp), (int32_t *)(base + o_pre), (int32_t *)(base + o_lens),
+                            (int32_t *)(base + o_sched), (float *)(base + o_ml), (float *)(base + o_o), nullptr};
+    hipStream_t st = (hipStream_t)stream;
+    // Nothing has to start at zero: every word of the array that a kernel of this call reads was written by an earlier
+    // kernel of the same call (queries of all batch rows incl. their zero padding, the whole schedule, every partial
+    // slot the combine visits), except the slack behind the last query, which only feeds masked-out positions.
+    if ((rc = hx_launch_pack_q(e, batch, q_dev, st, &bufs))) return rc;
+    if ((rc = hx_launch_step_setup(e, batch, nullptr, seq_lens, nullptr, 0, st, &bufs))) return rc;
+    if (kv->fp8) rc = hx_launch_attention_fp8(e, kv, layer, block_table, max_blocks, st, &bufs);
+    else rc = hx_launch_attention(e, kv, layer, batch, seq_lens, block_table, max_blocks, st, &bufs);
+    if (rc) return rc;
+    return hx_launch_combine(e, batch, out_dev, st, &bufs);
+}
+
 extern "C" int hx_stage_rmsnorm(hx_engine *e, int gain_kind, int layer, int32_t batch, const float *x_dev, float *y_dev,
                                 void *stream) {
     int rc = check_step_args(e, nullptr, batch, 1);

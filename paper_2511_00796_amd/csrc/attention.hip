@@ -70,13 +70,23 @@ __global__ __launch_bounds__(256) void step_setup_kernel(int batch, int n_kv, in
     }
 }
 
-int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
-                         const int32_t *table, int max_blocks, hipStream_t st) {
+hx_attn_bufs hx_attn_bufs_of(const hx_engine *e) {
     char *ws = e->ws;
-    hipLaunchKernelGGL(step_setup_kernel, dim3(batch + 1), dim3(256), 0, st, batch, e->cfg.n_kv_heads, e->attn_waves,
-                       positions, seq_lens, table, max_blocks, (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
-                       (int32_t *)(ws + e->map.sched), (int32_t *)(ws + e->map.blk_new), (float *)(ws + e->map.cs), e->D / 2,
-                       (double)e->cfg.rope_theta, e->cfg.max_batch);
+    return hx_attn_bufs{(uint16_t *)(ws + e->map.qp), (int32_t *)(ws + e->map.pre), (int32_t *)(ws + e->map.lens),
+                        (int32_t *)(ws + e->map.sched), (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o),
+                        (uint16_t *)(ws + e->map.ap)};
+}
+
+int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
+                         const int32_t *table, int max_blocks, hipStream_t st, const hx_attn_bufs *bufs) {
+    char *ws = e->ws;
+    const hx_attn_bufs own = hx_attn_bufs_of(e);
+    if (bufs && positions) return hx_fail(HX_E_RANGE, "the schedule-only set-up takes no positions");
+    const hx_attn_bufs &a = bufs ? *bufs : own;
+    // without positions only block 0 runs: the per-row blocks would write the engine's RoPE tables
+    hipLaunchKernelGGL(step_setup_kernel, dim3(positions ? batch + 1 : 1), dim3(256), 0, st, batch, e->cfg.n_kv_heads, e->attn_waves,
+                       positions, seq_lens, table, max_blocks, a.pre, a.lens, a.sched, (int32_t *)(ws + e->map.blk_new),
+                       (float *)(ws + e->map.cs), e->D / 2, (double)e->cfg.rope_theta, e->cfg.max_batch);
     HX_CHECK_LAUNCH("step_setup");
     return HX_OK;
 }
@@ -351,6 +361,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
         *(f32x4_t *)dst = f32x4_t{acc[0], acc[1], acc[2], acc[3]};
         *(f32x4_t *)(dst + 4) = f32x4_t{acc[4], acc[5], acc[6], acc[7]};
     }
+    if (ap == nullptr) return;
     uint4 pk;
     pk.x = hx_cvt_pk_bf16(acc[0], acc[1]); pk.y = hx_cvt_pk_bf16(acc[2], acc[3]);
     pk.z = hx_cvt_pk_bf16(acc[4], acc[5]); pk.w = hx_cvt_pk_bf16(acc[6], acc[7]);
@@ -358,18 +369,17 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
 }
 
 int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
-                        const int32_t *table, int max_blocks, hipStream_t st) {
+                        const int32_t *table, int max_blocks, hipStream_t st, const hx_attn_bufs *bufs) {
     const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
-    char *ws = e->ws;
+    const hx_attn_bufs own = hx_attn_bufs_of(e);
+    const hx_attn_bufs &a = bufs ? *bufs : own;
     const int n_kv = e->cfg.n_kv_heads;
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
     (void)seq_lens; (void)batch;
     dim3 grid(e->attn_waves), block(64);
 #define HX_ATTN_ARGS                                                                                             \
-    pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), table, max_blocks,                          \
-        (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
-        (const int32_t *)(ws + e->map.sched), n_kv, e->G, scale_log2e,                                           \
-        (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
+    pool_layer, kv->block_bytes, (const uint16_t *)a.qp, table, max_blocks, (const int32_t *)a.pre,              \
+        (const int32_t *)a.lens, (const int32_t *)a.sched, n_kv, e->G, scale_log2e, a.part_ml, a.part_o
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_kernel<128, 3>), grid, block, 0, st, HX_ATTN_ARGS);
     else             hipLaunchKernelGGL((attn_splitk_kernel<64, 4>), grid, block, 0, st, HX_ATTN_ARGS);
 #undef HX_ATTN_ARGS
@@ -377,15 +387,15 @@ int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batc
     return HX_OK;
 }
 
-int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st) {
-    char *ws = e->ws;
+int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st, const hx_attn_bufs *bufs) {
+    const hx_attn_bufs own = hx_attn_bufs_of(e);
+    const hx_attn_bufs &a = bufs ? *bufs : own;
     const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
     const int m_groups = hx_m_groups(batch);
     dim3 cgrid((batch * n_q + 3) / 4), cblock(256);
 #define HX_COMB_ARGS                                                                                             \
-    batch, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),             \
-        (const int32_t *)(ws + e->map.sched), (const float *)(ws + e->map.part_ml),                              \
-        (const float *)(ws + e->map.part_o), (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out
+    batch, n_q, n_kv, e->G, (const int32_t *)a.pre, (const int32_t *)a.lens, (const int32_t *)a.sched,            \
+        (const float *)a.part_ml, (const float *)a.part_o, a.ap, m_groups, attn_f32_out
     if (e->D == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, cblock, 0, st, HX_COMB_ARGS);
     else             hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, cblock, 0, st, HX_COMB_ARGS);
 #undef HX_COMB_ARGS

@@ -209,16 +209,15 @@ __global__ __launch_bounds__(64) void attn_splitk_fp8_kernel(const char *__restr
 }
 
 int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
-                            hipStream_t st) {
+                            hipStream_t st, const hx_attn_bufs *bufs) {
     const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
-    char *ws = e->ws;
+    const hx_attn_bufs own = hx_attn_bufs_of(e);
+    const hx_attn_bufs &a = bufs ? *bufs : own;
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
     dim3 grid(e->attn_waves), block(64);
 #define HX_ATTN8_ARGS                                                                                            \
-    pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), table, max_blocks,                          \
-        (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
-        (const int32_t *)(ws + e->map.sched), e->cfg.n_kv_heads, e->G, scale_log2e,                              \
-        (float *)(ws + e->map.part_ml), (float *)(ws + e->map.part_o)
+    pool_layer, kv->block_bytes, (const uint16_t *)a.qp, table, max_blocks, (const int32_t *)a.pre,              \
+        (const int32_t *)a.lens, (const int32_t *)a.sched, e->cfg.n_kv_heads, e->G, scale_log2e, a.part_ml, a.part_o
     // ring depths: 128: see the header; 64: depth 6 (every depth from 2 to 12 is right since the operand hold is
     // ordered behind the products; the tests cover long runs)
     if (e->D == 128) hipLaunchKernelGGL((attn_splitk_fp8_kernel<128, 4>), grid, block, 0, st, HX_ATTN8_ARGS);

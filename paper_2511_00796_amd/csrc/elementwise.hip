@@ -198,10 +198,10 @@ int hx_launch_unpack_q(const hx_engine *e, int batch, float *q_out, hipStream_t 
     HX_CHECK_LAUNCH("unpack_q");
     return HX_OK;
 }
-int hx_launch_pack_q(const hx_engine *e, int batch, const float *q, hipStream_t st) {
+int hx_launch_pack_q(const hx_engine *e, int batch, const float *q, hipStream_t st, const hx_attn_bufs *bufs) {
     int64_t n = (int64_t)batch * e->cfg.n_kv_heads * 16 * e->D;
     hipLaunchKernelGGL(q_pack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (float *)q,
-                       (uint16_t *)(e->ws + e->map.qp), batch, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->D, false);
+                       bufs ? bufs->qp : (uint16_t *)(e->ws + e->map.qp), batch, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->D, false);
     HX_CHECK_LAUNCH("pack_q");
     return HX_OK;
 }

@@ -230,6 +230,17 @@ struct hx_kv {
     size_t layer_bytes;     // num_blocks * block_bytes
 };
 
+// Device buffers of the attention stage beyond its inputs and outputs: the packed queries, the per-step schedule and
+// the split-K partial results.  They live in the engine's workspace (hx_attn_bufs_of) or, for the entry point that
+// must not depend on a workspace, in the library's static device array.
+struct hx_attn_bufs {
+    uint16_t *qp;               // packed queries
+    int32_t *pre, *lens, *sched;
+    float *part_ml, *part_o;
+    uint16_t *ap;               // packed bf16 attention output for the output projection; NULL: not written
+};
+hx_attn_bufs hx_attn_bufs_of(const hx_engine *e);
+
 // ---- kernel launchers (one per translation unit) ---------------------------------------------------
 
 // kv_cache.hip
@@ -240,11 +251,13 @@ int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int ba
                           int splits, size_t split_stride, const int32_t *positions, hipStream_t st);
 
 // attention.hip
+// bufs: NULL = the engine's workspace
 int hx_launch_step_setup(const hx_engine *e, int batch, const int32_t *positions, const int32_t *seq_lens,
-                         const int32_t *table, int max_blocks, hipStream_t st);   // table may be NULL when positions is
+                         const int32_t *table, int max_blocks, hipStream_t st,   // table may be NULL when positions is
+                         const hx_attn_bufs *bufs = nullptr);                    // (bufs: positions must be NULL)
 int hx_launch_attention(const hx_engine *e, const hx_kv *kv, int layer, int batch, const int32_t *seq_lens,
-                        const int32_t *table, int max_blocks, hipStream_t st);
-int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st);
+                        const int32_t *table, int max_blocks, hipStream_t st, const hx_attn_bufs *bufs = nullptr);
+int hx_launch_combine(const hx_engine *e, int batch, float *attn_f32_out, hipStream_t st, const hx_attn_bufs *bufs = nullptr);
 
 // gemm.hip
 int hx_launch_pack_matrix(const hx_engine *e, const hx_matrix *m, const void *src, int64_t rows, int64_t cols,
@@ -284,7 +297,7 @@ int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out,
 
 // attention_fp8.hip: the decode step's attention over an 8-bit cache
 int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
-                            hipStream_t st);
+                            hipStream_t st, const hx_attn_bufs *bufs = nullptr);
 
 // sampling.hip
 int hx_launch_nucleus(const hx_engine *e, int batch, const float *logits, const hx_sample_params *sample,
@@ -303,7 +316,7 @@ int hx_launch_reduce_norm(const hx_engine *e, int batch, const float *ypart, int
 int hx_launch_pack_x(const hx_engine *e, int batch, const float *x, int K, void *xp, hipStream_t st);
 int hx_launch_unpack_x(const hx_engine *e, int batch, const void *xp, int K, float *x, hipStream_t st);
 int hx_launch_unpack_q(const hx_engine *e, int batch, float *q_out, hipStream_t st);
-int hx_launch_pack_q(const hx_engine *e, int batch, const float *q, hipStream_t st);
+int hx_launch_pack_q(const hx_engine *e, int batch, const float *q, hipStream_t st, const hx_attn_bufs *bufs = nullptr);
 int hx_launch_sum_partials(const hx_engine *e, int batch, const float *ypart, int splits, size_t split_stride,
                            int N, float *y, hipStream_t st);
 int hx_launch_norm_only(const hx_engine *e, int batch, const float *x, size_t gain_off, float *y, hipStream_t st);
