@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--workload", default="7b-b128",
                     help="1.5b-b64, 1.5b-b256-longtail, 7b-b128 (default, the configuration the metric is quoted on) or "
                          "14b-b64; tiny-b4 fits the caches and is a parity case only")
+    ap.add_argument("--batch", type=int, default=0, metavar="B",
+                    help="override the workload's batch (same model shape and length law; reported as <workload>@bB): how "
+                         "the kernels behave at other row counts, e.g. 4 rows = one m-group")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16,
@@ -144,6 +147,9 @@ def main():
               % ", ".join(n for n, w in synth.WORKLOADS.items() if w.kv_fill == "normal"), file=sys.stderr)
         sys.exit(2)
     wl = synth.WORKLOADS[args.workload]
+    if args.batch:
+        import dataclasses
+        wl = dataclasses.replace(wl, batch=args.batch, name="%s@b%d" % (wl.name, args.batch))
     s = wl.shape
     ctx = synth.context_lengths(wl)
     if args.cpu_layers <= 0 or args.cpu_layers > s.n_layers:
@@ -347,6 +353,8 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None if fp8 else measured_traffic(wl.name),
                      "traffic_unit": "bytes per launch",
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this kernel source, scaled by a "
+                                       "plain copy: profiles/attn_splitk_7b-b128_hbm_traffic.txt (null once the source changed)",
                      "launches_timed": int(attn_n), "avg_launch_ms": attn_avg_ms,
                      "algorithmic_bytes_per_launch": kv_bytes_per_launch},
         "step_spread_ms": {"min": per_step[0], "median": per_step[len(per_step) // 2], "max": per_step[-1]},
