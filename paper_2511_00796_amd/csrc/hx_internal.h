@@ -14,7 +14,8 @@
 //    i.e. the B operand (16 k x 32 columns m) of the same instruction.
 //
 //  * packed query of one (sequence, KV head): [kk][lane][8 bf16], kk < head_dim/32:
-//        element (lane, j) = q[head = kvh*G + lane%16][32*kk + 8*(lane/16) + j], zero for lane%16 >= G
+//        element (lane, j) = q[head = kvh*G + lane%16][32*kk + 8*(lane/16) + j]; lanes with lane%16 >= G are never
+//        written or interpreted (they only feed accumulator columns that nobody reads)
 //    i.e. the B operand (32 k x 16 columns g) of v_mfma_f32_16x16x32_bf16.
 //
 //  * KV pool: [layer][block][kv_head][K tile | V tile]; a tile holds 16 tokens x head_dim:
