@@ -491,6 +491,14 @@ static int launch_shape(int wn, int wk, int epilogue, dim3 grid, hipStream_t st,
         if (wn == 6) return launch_epi<MG, 6, 1>(epilogue, grid, st, a);
     }
     if (wn == 4 && wk == 2) return launch_epi<MG, 4, 2>(epilogue, grid, st, a);
+    if constexpr (MG <= 4) {
+        // ten n-tiles per workgroup (twelve wavefronts): only for products that run in several rounds (the LM head)
+        if (wn == 10 && wk == 1 && epilogue != HX_EPI_PARTIAL) {
+            if (epilogue == HX_EPI_SWIGLU) return launch_one<MG, 10, 1, HX_EPI_SWIGLU>(grid, st, a);
+            if (epilogue == HX_EPI_SAMPLE) return launch_one<MG, 10, 1, HX_EPI_SAMPLE>(grid, st, a);
+            return launch_one<MG, 10, 1, HX_EPI_LOGITS>(grid, st, a);
+        }
+    }
     return hx_fail(HX_E_RANGE, "unsupported product shape wn=%d wk=%d for %d m-groups", wn, wk, MG);
 }
 
@@ -498,11 +506,16 @@ static int launch_shape(int wn, int wk, int epilogue, dim3 grid, hipStream_t st,
 // A workgroup occupies a whole compute unit (128 KiB of LDS), so a launch runs in rounds of as many workgroups as
 // the device has compute units (hx_device_cus) and a partly filled last round costs a full one.  Measured on MI355X, wn x 1 shapes (wn n-tiles
 // sharing one activation stream, 32 KiB stages, a barrier every 8 k-steps) are the fastest.  The planner
-// picks wn in {4, 5, 6} -- and, for products whose consumer kernel sums split partials, the number of
-// K-splits (at most HX_MAX_SPLITS, at least 16 k-steps each) -- that minimises rounds x tiles per
-// workgroup, i.e. the time of the busiest compute unit; ties go to the smaller wn and fewer splits.
-// Example: the 1184 tiles of the 7B gate|up matrix make 296 workgroups of 4 (two rounds on 256 compute
-// units) but 237 workgroups of 5 (one round).  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
+// picks wn in {4, 5, 6, 10} -- and, for products whose consumer kernel sums split partials, the number of
+// K-splits (at most HX_MAX_SPLITS, at least 16 k-steps each) -- that minimises the time of the busiest compute
+// unit: rounds x (wn tiles + 3 tile-times for the round's own copy of the activations, which every workgroup
+// draws from the L2 whatever its width) x whole ring revolutions; split products, which run in one round and
+// read only a K-slice of the activations, and 256-row products keep a small charge per extra tile instead (five
+// consumers on four SIMDs); ties go to the smaller wn and fewer splits.
+// Examples: the 1184 tiles of the 7B gate|up matrix make 296 workgroups of 4 (two rounds on 256 compute
+// units) but 237 workgroups of 5 (one round); the 4752 tiles of the LM head make five rounds of 4, four of 5 or
+// two of 10, measured 253 / 244 / 230 us.  Ten tiles per workgroup are twelve wavefronts (three per SIMD): only
+// for products without split partials and up to 128 rows.  HX_GEMM_SHAPE="wn,wk,splits" overrides (tuning).
 
 struct gemm_launch { int wn, wk, splits, tile0, tiles; };
 
@@ -512,16 +525,19 @@ static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_lau
     double best_cost = 1e300;
     int max_s = partial ? HX_MAX_SPLITS : 1;
     if (const char *cap = getenv("HX_GEMM_MAX_SPLITS")) max_s = partial ? std::max(1, std::min(HX_MAX_SPLITS, atoi(cap))) : 1;
-    for (int wn = 4; wn <= 6; ++wn) {
+    static const int widths[] = {4, 5, 6, 10};
+    for (int wn : widths) {
+        if (wn == 10 && (partial || mg > 4)) continue;
         for (int s = 1; s <= max_s; ++s) {
             if (s > 1 && k_steps / s < 16) break;
             const int wgs = ((n_tiles + wn - 1) / wn) * s;
             const int rounds = (wgs + cus - 1) / cus;
             const int sps = (k_steps + s - 1) / s;
-            // busiest compute unit: rounds x wn tiles x whole ring revolutions (one more to fill the ring), plus
-            // a small charge per split for writing and re-reading its partial tile
+            // busiest compute unit: rounds x (wn tiles + the activations) x whole ring revolutions (one more to fill
+            // the ring), plus a small charge per split for writing and re-reading its partial tile
             const int revolutions = (sps + HX_GEMM_RING - 1) / HX_GEMM_RING + 1;
-            const double cost = (double)rounds * (wn + 0.35 * (wn - 4)) * revolutions * (1.0 + 0.02 * (s - 1));
+            const double width = (partial || mg > 4) ? wn + 0.35 * (wn - 4) : wn + 3.0;   // as measured on each kind
+            const double cost = (double)rounds * width * revolutions * (1.0 + 0.02 * (s - 1));
             if (cost < best_cost - 1e-9) { best_cost = cost; best.wn = wn; best.splits = s; }
         }
     }
@@ -531,7 +547,6 @@ static int plan_product(int n_tiles, int k_steps, int mg, bool partial, gemm_lau
         ((b == 1 && a >= 4 && a <= 6) || (a == 4 && b == 2))) {
         best.wn = a; best.wk = b; best.splits = c;
     }
-    (void)mg;
     out[0] = best;
     return 1;
 }

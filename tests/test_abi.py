@@ -108,9 +108,9 @@ def test_engine_create_validates_buffers_on_the_host():
 
 def test_product_plans_fill_the_chip_and_respect_their_limits():
     """Host-side launch planner: every plan keeps at least 16 k-steps per split, never splits a product whose epilogue
-    needs the whole sum, stays within 9 splits and 4..6 tiles per workgroup, and for the 7B shapes picks the plans the
-    design rests on (gate|up: 237 workgroups of 5 = one round on 256 compute units; O and QKV: 7 splits of exactly two
-    ring revolutions; down: 9 splits)."""
+    needs the whole sum, stays within 9 splits and 4..6 tiles per workgroup (10 only for unsplit products of up to 128 rows),
+    and for the 7B shapes picks the plans the design rests on (gate|up: 237 workgroups of 5 = one round on 256 compute
+    units; O and QKV: 7 splits of exactly two ring revolutions; down: 9 splits; LM head: two rounds of 10 tiles)."""
     lib = binding.load()
 
     def plan(n_tiles, k_steps, batch, partial):
@@ -123,7 +123,7 @@ def test_product_plans_fill_the_chip_and_respect_their_limits():
                               (s.intermediate, s.hidden, True), (s.hidden, s.vocab, False)):
             for batch in (1, 4, 64, 128, 256):
                 wn, wk, sp = plan((N + 31) // 32, K // 16, batch, partial)
-                assert 4 <= wn <= 6 and wk == 1 and 1 <= sp <= 9
+                assert (4 <= wn <= 6 or (wn == 10 and not partial and batch <= 128)) and wk == 1 and 1 <= sp <= 9
                 assert sp == 1 or (K // 16) // sp >= 16
                 assert partial or sp == 1
     s = synth.QWEN_7B
@@ -131,6 +131,8 @@ def test_product_plans_fill_the_chip_and_respect_their_limits():
     assert plan(s.hidden // 32, s.q_dim // 16, 128, True) == (4, 1, 7)
     assert plan(s.qkv_dim // 32, s.hidden // 16, 128, True) == (4, 1, 7)
     assert plan(s.hidden // 32, s.intermediate // 16, 128, True) == (4, 1, 9)
+    assert plan(s.vocab // 32, s.hidden // 16, 128, False) == (10, 1, 1)
+    assert plan(s.vocab // 32, s.hidden // 16, 256, False) == (4, 1, 1)
     none = C.c_int32()
     assert lib.hx_plan_product(0, 10, 4, 1, C.byref(none), C.byref(none), C.byref(none)) == binding.HX_E_RANGE
     assert lib.hx_plan_product(10, 10, 300, 1, C.byref(none), C.byref(none), C.byref(none)) == binding.HX_E_RANGE
