@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--prefill-streams", type=int, default=1, choices=[1, 2, 4], metavar="S",
                     help="with --prefill: S engines over one copy of the packed weights, each with its own workspace, "
                          "cache and stream, processing different prompts concurrently")
+    ap.add_argument("--prefill-rows-per-call", type=int, default=256, metavar="M",
+                    help="with --prefill: rows per call; above 256 (a multiple of 256 that divides P) the calls go through "
+                         "prefill_rows, whose products run over all rows of the call at once")
     ap.add_argument("--prefill-rows-per-seq", type=int, default=256, metavar="N",
                     help="with --prefill: consecutive positions of one prompt per call (256 = one prompt per call, "
                          "2 = all 128 prompts in every call)")
@@ -206,6 +209,53 @@ def main():
             k2 = binding.KVCache(e2, nb)
             k2.pool.zero_()
             lanes.append((e2, k2, torch.cuda.Stream()))
+        if args.prefill_rows_per_call > 256:
+            # M consecutive positions of one prompt per call, through prefill_rows
+            M = args.prefill_rows_per_call
+            assert M % 256 == 0 and P % M == 0 and n_streams == 1
+            table_d = torch.from_numpy(table).cuda()
+            toks = torch.randint(0, s.vocab, (M,), dtype=torch.int32, device="cuda")
+            pos_of_call = [torch.arange(M, dtype=torch.int32, device="cuda") + c * M for c in range(P // M)]
+            len_of_call = [p + 1 for p in pos_of_call]
+            wide_ws = torch.empty(binding.prefill_workspace_bytes(eng.cfg, M), dtype=torch.uint8, device="cuda")
+            n_seq = min(B, 32)                                    # 32 prompts are enough for a steady figure
+            rows_of_seq = [table_d[g:g + 1].expand(M, -1).contiguous() for g in range(n_seq)]
+            calls = n_seq * (P // M)
+            torch.cuda.synchronize()
+
+            def run_wide():
+                for g in range(n_seq):
+                    for c in range(P // M):
+                        eng.prefill_rows(kvc, toks, pos_of_call[c], len_of_call[c], rows_of_seq[g], wide_ws)
+
+            run_wide()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run_wide()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            eng.profile_enable(["gemm_gate_up"])
+            for c in range(2):
+                eng.prefill_rows(kvc, toks, pos_of_call[c % (P // M)], len_of_call[c % (P // M)], rows_of_seq[0], wide_ws)
+            torch.cuda.synchronize()
+            gu_ms, gu_n = eng.profile_read("gemm_gate_up")
+            eng.profile_enable([])
+            gu_avg_ms = gu_ms / max(gu_n, 1)
+            gu_flops = 2.0 * M * s.hidden * 2 * s.intermediate
+            call_flops = 2.0 * M * (s.weight_elements() - s.hidden * s.vocab)
+            print(json.dumps({"metric": "prompt tokens/s through prefill_rows (rows = prompt tokens)",
+                              "value": M * calls / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
+                              "rows_per_call": M, "ms_per_call": dt / calls * 1e3,
+                              "config": {"workload": "%s-prefill" % s.name, "prompts": n_seq, "prompt_len": P, "rows_per_call": M,
+                                         "kv_cache": "fp8-e4m3" if args.kv_dtype == "fp8" else "bf16"},
+                              "data": "synthetic", "dtype": "bf16",
+                              "product_flops_over_call_time_TFLOPs": call_flops / (dt / calls) / 1e12,
+                              "roofline": {"kernel": "gemm_wide_kernel (gate|up product over all rows of the call)", "bound": "mfma",
+                                           "achieved": gu_flops / (gu_avg_ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                                           "frac": gu_flops / (gu_avg_ms * 1e-3) / 1e12 / 2500.0, "traffic": None,
+                                           "launches_timed": int(gu_n), "avg_launch_ms": gu_avg_ms,
+                                           "algorithmic_flops_per_launch": gu_flops}}))
+            return
         per_seq = args.prefill_rows_per_seq                  # consecutive positions of each sequence per call
         assert R % per_seq == 0 and P % per_seq == 0 and B % (R // per_seq) == 0
         seqs_per_call = R // per_seq

@@ -226,6 +226,23 @@ int decode_step_top_p(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t
 int prefill_chunk(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *stream);
 
+/* Prompt processing for many rows per call: prefill_chunk for n_rows = a multiple of 256, at most HX_PREFILL_MAX_ROWS,
+   with every matrix product taken over ALL rows at once (both operands tiled through LDS), so that the weights are
+   read from memory once per call instead of once per 256 rows (paper Section 1, stage (i); Section 4.2.2: a rollout
+   starts from its prompt).  Rows, tables and results exactly as prefill_chunk (rows r of block r / 256; K and V of all
+   rows of the call enter the cache before any row attends); the attention output capture, if set, is
+   [n_layers, n_rows, n_q_heads * head_dim].  The engine must have been created with max_batch = 256 and its hidden,
+   intermediate and n_q_heads * head_dim sizes must be multiples of 32.  workspace_dev: DEVICE memory, 256-byte aligned,
+   of at least hx_prefill_workspace_bytes(cfg, n_rows) bytes, owned by the caller, overwritten by the call (the
+   engine's own workspace is not used; two calls on different streams need different workspaces).  Nothing is allocated
+   and the host is not synchronised.  Errors: HX_E_RANGE for n_rows, alignment or a short workspace, HX_E_SHAPE for the
+   size conditions, HX_E_NULL.  The remainder of a prompt (fewer than 256 rows) goes through prefill_chunk. */
+#define HX_PREFILL_MAX_ROWS 8192
+int hx_prefill_workspace_bytes(const hx_model_config *cfg, int32_t max_rows, size_t *bytes_out);
+int prefill_rows(hx_engine *engine, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
+                 const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks_per_seq, void *workspace_dev,
+                 size_t workspace_bytes, void *stream);
+
 /* Checks the DEVICE-side inputs of a step before it is launched; decode_step itself trusts them (a wrong block id
    or length makes its kernels read or write outside the pool).  Verified per row: 0 <= token < vocab;
    0 <= position < max_seq_len and position < 16 * max_blocks_per_seq; seq_len == position + 1; every block id

@@ -21,7 +21,8 @@ HX_OK, HX_E_NULL, HX_E_CONFIG, HX_E_SHAPE, HX_E_ALIGN, HX_E_TOO_SMALL, HX_E_RANG
 
 EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_bytes", "hx_engine_create",
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
-           "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
+           "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "prefill_rows", "hx_prefill_workspace_bytes",
+           "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
            "hx_stage_rope_append", "hx_stage_attention", "hx_stage_attention_static", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
            "hx_profile_enable", "hx_profile_sample_every", "hx_profile_read"]
 
@@ -75,6 +76,8 @@ def load():
         "hx_kv_gather": [vp, C.c_int, vp, vp, vp, vp, i32, i32, i64, vp],
         "decode_step": [vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp],
         "prefill_chunk": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
+        "prefill_rows": [vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp],
+        "hx_prefill_workspace_bytes": [cfgp, i32, C.POINTER(sz)],
         "hx_validate_step_inputs": [vp, vp, i32, vp, vp, vp, vp, i32, vp],
         "decode_step_sample": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "decode_step_top_p": [vp, vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp, vp],
@@ -127,6 +130,12 @@ def make_config(shape, max_batch: int, max_seq_len: int, kv_dtype: int = HX_KV_B
 def weights_bytes(cfg: ModelConfig) -> int:
     out = C.c_size_t()
     _check(load().hx_weights_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def prefill_workspace_bytes(cfg: ModelConfig, max_rows: int) -> int:
+    out = C.c_size_t()
+    _check(load().hx_prefill_workspace_bytes(C.byref(cfg), max_rows, C.byref(out)))
     return out.value
 
 
@@ -205,6 +214,13 @@ class Engine:
         """Rows = prompt tokens (<= max_batch); block_table holds one table row per ROW."""
         _check(load().prefill_chunk(self.handle, kv.handle, tokens.numel(), _ptr(tokens), _ptr(positions), _ptr(seq_lens),
                                     _ptr(block_table), block_table.shape[1], _stream()))
+
+    def prefill_rows(self, kv: "KVCache", tokens, positions, seq_lens, block_table, workspace: torch.Tensor) -> None:
+        """prefill_chunk for a multiple of 256 rows with the products over all rows at once; `workspace` is a device
+        byte tensor of at least prefill_workspace_bytes(cfg, rows) bytes."""
+        _check(load().prefill_rows(self.handle, kv.handle, tokens.numel(), _ptr(tokens), _ptr(positions), _ptr(seq_lens),
+                                   _ptr(block_table), block_table.shape[1], _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream()))
 
     def decode_step_sample(self, kv: "KVCache", tokens, positions, seq_lens, block_table, temperature: float, seed: int,
                            logits: Optional[torch.Tensor], out_tokens: torch.Tensor, out_logprobs: torch.Tensor,

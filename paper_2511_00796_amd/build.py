@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libhexdecode.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "kv_cache.hip", "attention.hip", "attention_chunk.hip", "attention_fp8.hip", "gemm.hip", "elementwise.hip", "sampling.hip"]
+SOURCES = ["api.hip", "kv_cache.hip", "attention.hip", "attention_chunk.hip", "attention_fp8.hip", "gemm.hip", "gemm_wide.hip", "elementwise.hip", "sampling.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: products and sums round separately unless fmaf is written out;
 # packed fp32 instructions are switched off for the device pass.

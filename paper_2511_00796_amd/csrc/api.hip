@@ -489,6 +489,96 @@ extern "C" int prefill_chunk(hx_engine *e, hx_kv *kv, int32_t n_rows, const int3
                     false, stream);
 }
 
+// ---- prompt rows in blocks of 256, the products over all blocks at once ------------------------------------------
+// Each block of 256 rows has a workspace of its own, laid out like the engine's; a shallow copy of the engine that
+// points at it lets every row kernel and the attention run per block exactly as in prefill_chunk, while each matrix
+// product is ONE launch over all blocks (gemm_wide.hip), so a weight is read once per call.
+static size_t wide_block_stride(const hx_engine *e) { return align_up(e->map.total, 4096); }
+
+extern "C" int hx_prefill_workspace_bytes(const hx_model_config *cfg, int32_t max_rows, size_t *out) {
+    if (!out) return hx_fail(HX_E_NULL, "out is NULL");
+    hx_engine e;
+    int rc = init_engine_shape(&e, cfg);
+    if (rc) return rc;
+    if (cfg->max_batch != 256) return hx_fail(HX_E_RANGE, "prefill_rows needs an engine with max_batch 256, not %d", cfg->max_batch);
+    if (max_rows < 256 || max_rows > HX_PREFILL_MAX_ROWS || max_rows % 256)
+        return hx_fail(HX_E_RANGE, "max_rows %d is not a multiple of 256 in [256, %d]", max_rows, HX_PREFILL_MAX_ROWS);
+    map_weights(&e);
+    map_workspace(&e);
+    *out = (size_t)(max_rows / 256) * wide_block_stride(&e);
+    return HX_OK;
+}
+
+extern "C" int prefill_rows(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32_t *tokens, const int32_t *positions,
+                            const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks, void *workspace_dev,
+                            size_t workspace_bytes, void *stream) {
+    if (!e || !kv) return hx_fail(HX_E_NULL, "engine or kv is NULL");
+    if (kv->engine != e) return hx_fail(HX_E_SHAPE, "kv belongs to another engine");
+    if (!tokens || !positions || !seq_lens || !block_table || !workspace_dev) return hx_fail(HX_E_NULL, "a device pointer argument is NULL");
+    const hx_model_config *c = &e->cfg;
+    if (c->max_batch != 256) return hx_fail(HX_E_RANGE, "prefill_rows needs an engine with max_batch 256, not %d", c->max_batch);
+    if (n_rows < 256 || n_rows > HX_PREFILL_MAX_ROWS || n_rows % 256)
+        return hx_fail(HX_E_RANGE, "n_rows %d is not a multiple of 256 in [256, %d] (prefill_chunk takes the remainder)", n_rows,
+                       HX_PREFILL_MAX_ROWS);
+    if (max_blocks < 1) return hx_fail(HX_E_RANGE, "max_blocks_per_seq %d must be positive", max_blocks);
+    if (c->hidden % 32 || c->intermediate % 32 || e->q_dim % 32)
+        return hx_fail(HX_E_SHAPE, "prefill_rows needs hidden, intermediate and n_q_heads * head_dim to be multiples of 32");
+    const int R = n_rows / 256;
+    const size_t stride = wide_block_stride(e);
+    if ((uintptr_t)workspace_dev % 256) return hx_fail(HX_E_RANGE, "workspace is not 256-byte aligned");
+    if (workspace_bytes < (size_t)R * stride)
+        return hx_fail(HX_E_RANGE, "workspace holds %zu bytes, %d rows need %zu (hx_prefill_workspace_bytes)", workspace_bytes, n_rows,
+                       (size_t)R * stride);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws0 = (char *)workspace_dev;
+    std::vector<hx_engine> view(R, *e);                  // shallow copies: same weights, schedule sizes and hooks
+    for (int b = 0; b < R; ++b) { view[b].ws = ws0 + (size_t)b * stride; view[b].ws_bytes = stride; }
+    const hx_ws_map &m = e->map;
+    const size_t attn_stride = (size_t)n_rows * e->q_dim;
+    int rc;
+    auto rows = [&](const int32_t *p, int b) { return p + (size_t)b * 256; };
+    auto table = [&](int b) { return block_table + (size_t)b * 256 * max_blocks; };
+    const bool chunked = e->chunk_attention;
+
+    // The schedules are per block (one small launch each); the row kernels take all blocks in one launch (their
+    // block dimension strides through the workspaces), as do the products; the attention runs block by block.
+    const hx_engine *v0 = &view[0];
+    const float *ypart0 = (const float *)(ws0 + m.ypart);
+    for (int b = 0; b < R; ++b) {
+        const hx_engine *vb = &view[b];
+        HX_TIMED(HX_K_SETUP, hx_launch_step_setup(vb, 256, rows(positions, b), rows(seq_lens, b), table(b), max_blocks, st));
+        if (chunked) HX_TIMED(HX_K_SETUP, hx_launch_chunk_setup(vb, 256, rows(seq_lens, b), table(b), max_blocks, st));
+    }
+    HX_TIMED(HX_K_NORM, hx_launch_embed_norm(v0, 256, tokens, e->layers[0].g1, st, R, stride));
+    for (int l = 0; l < c->n_layers; ++l) {
+        const hx_layer_map *lm = &e->layers[l];
+        const int s_qkv = hx_wide_splits(&lm->wqkv, R), s_o = hx_wide_splits(&lm->wo, R), s_d = hx_wide_splits(&lm->wd, R);
+        HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm_wide(e, &lm->wqkv, R, ws0, stride, m.xp, HX_EPI_PARTIAL, m.ypart, 0, s_qkv, st));
+        // K and V of every row of the call enter the cache before any row attends
+        HX_TIMED(HX_K_ROPE, hx_launch_rope_append(v0, kv, l, 256, ypart0, s_qkv, (size_t)256 * e->qkv_dim, positions, st, R, stride));
+        if (l + 1 == c->n_layers) break;     // of the last layer only its K and V are needed
+        float *capture = e->attn_capture ? e->attn_capture + l * attn_stride : nullptr;
+        for (int b = 0; b < R; ++b) {
+            const hx_engine *vb = &view[b];
+            if (chunked) {
+                HX_TIMED(HX_K_ATTENTION, hx_launch_chunk_attention(vb, kv, l, table(b), max_blocks, st));
+            } else {
+                if (kv->fp8) HX_TIMED(HX_K_ATTENTION, hx_launch_attention_fp8(vb, kv, l, table(b), max_blocks, st));
+                else HX_TIMED(HX_K_ATTENTION, hx_launch_attention(vb, kv, l, 256, rows(seq_lens, b), table(b), max_blocks, st));
+                HX_TIMED(HX_K_COMBINE, hx_launch_combine(vb, 256, capture ? capture + (size_t)b * 256 * e->q_dim : nullptr, st));
+            }
+        }
+        if (chunked) HX_TIMED(HX_K_COMBINE, hx_launch_chunk_combine(v0, 256, capture, st, R, stride));
+        HX_TIMED(HX_K_GEMM_O, hx_launch_gemm_wide(e, &lm->wo, R, ws0, stride, m.ap, HX_EPI_PARTIAL, m.ypart, 0, s_o, st));
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(v0, 256, ypart0, s_o, (size_t)256 * c->hidden, lm->g2, st, R, stride));
+        HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm_wide(e, &lm->wgu, R, ws0, stride, m.xp, HX_EPI_SWIGLU, 0, m.mp, 1, st));
+        HX_TIMED(HX_K_GEMM_DOWN, hx_launch_gemm_wide(e, &lm->wd, R, ws0, stride, m.mp, HX_EPI_PARTIAL, m.ypart, 0, s_d, st));
+        const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
+        HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(v0, 256, ypart0, s_d, (size_t)256 * c->hidden, next_gain, st, R, stride));
+    }
+    return HX_OK;
+}
+
 extern "C" int decode_step_sample(hx_engine *e, hx_kv *kv, int32_t batch, const int32_t *tokens, const int32_t *positions,
                                   const int32_t *seq_lens, const int32_t *block_table, int32_t max_blocks,
                                   float temperature, uint64_t seed, const int32_t *row_ids, float *logits_out,

@@ -381,9 +381,20 @@ __global__ __launch_bounds__(256) void attn_chunk_combine_kernel(int n_rows, int
                                                                  const float *__restrict__ part_ml,
                                                                  const float *__restrict__ part_o,
                                                                  uint16_t *__restrict__ ap, int m_groups,
-                                                                 float *__restrict__ attn_f32) {
+                                                                 float *__restrict__ attn_f32, size_t block_stride) {
     const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= n_rows * n_q) return;
+    if (blockIdx.y) {               // further row blocks of a wide prompt call: same layout, block_stride bytes apart
+        const size_t off = (size_t)blockIdx.y * block_stride;
+        pre = (const int32_t *)((const char *)pre + off);
+        lens = (const int32_t *)((const char *)lens + off);
+        sched = (const int32_t *)((const char *)sched + off);
+        rgrp = (const int32_t *)((const char *)rgrp + off);
+        part_ml = (const float *)((const char *)part_ml + off);
+        part_o = (const float *)((const char *)part_o + off);
+        ap = (uint16_t *)((char *)ap + off);
+        if (attn_f32) attn_f32 += (size_t)blockIdx.y * n_rows * n_q * D;
+    }
     const int lane = threadIdx.x & 63, d8 = lane & 15, ph = lane >> 4;
     const bool has_d = d8 < D / 8;
     const int b = bh / n_q, h = bh % n_q;
@@ -475,16 +486,16 @@ int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, co
     return HX_OK;
 }
 
-int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st) {
+int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st, int blocks, size_t block_stride) {
     char *ws = e->ws;
     const int n_kv = e->cfg.n_kv_heads, n_q = e->cfg.n_q_heads;
     const int m_groups = hx_m_groups(n_rows);
-    dim3 cgrid((n_rows * n_q + 3) / 4), cblock(256);
+    dim3 cgrid((n_rows * n_q + 3) / 4, blocks), cblock(256);
 #define HX_CCOMB_ARGS                                                                                            \
     n_rows, n_q, n_kv, e->G, (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),            \
         (const int32_t *)(ws + e->map.sched), (const int32_t *)(ws + e->map.chunk_rgrp),                         \
         (const float *)(ws + e->map.chunk_part_ml), (const float *)(ws + e->map.chunk_part_o),                   \
-        (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out
+        (uint16_t *)(ws + e->map.ap), m_groups, attn_f32_out, block_stride
     if (e->D == 128) hipLaunchKernelGGL((attn_chunk_combine_kernel<128>), cgrid, cblock, 0, st, HX_CCOMB_ARGS);
     else             hipLaunchKernelGGL((attn_chunk_combine_kernel<64>), cgrid, cblock, 0, st, HX_CCOMB_ARGS);
 #undef HX_CCOMB_ARGS

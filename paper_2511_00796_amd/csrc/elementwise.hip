@@ -31,9 +31,16 @@ __global__ __launch_bounds__(HX_NORM_THREADS) void norm_kernel(float *__restrict
                                                               const float *__restrict__ ypart, int splits,
                                                               size_t split_stride, const uint16_t *__restrict__ gain,
                                                               int H, float eps, uint16_t *__restrict__ xp, int m_groups,
-                                                              float *__restrict__ y_f32) {
+                                                              float *__restrict__ y_f32, size_t block_stride) {
     __shared__ float red[8];
     const int b = blockIdx.x;
+    if (blockIdx.y) {               // further row blocks of a wide prompt call: same layout, block_stride bytes apart
+        const size_t off = (size_t)blockIdx.y * block_stride;
+        x = (float *)((char *)x + off);
+        if (ypart) ypart = (const float *)((const char *)ypart + off);
+        xp = (uint16_t *)((char *)xp + off);
+        if (tokens) tokens += (size_t)blockIdx.y * gridDim.x;
+    }
     float v[HX_NORM_MAX_IT][8];
     float ss = 0.f;
 #pragma unroll
@@ -114,21 +121,22 @@ __global__ __launch_bounds__(HX_NORM_THREADS) void norm_kernel(float *__restrict
     }
 }
 
-int hx_launch_embed_norm(const hx_engine *e, int batch, const int32_t *tokens, size_t gain_off, hipStream_t st) {
-    hipLaunchKernelGGL((norm_kernel<0>), dim3(batch), dim3(HX_NORM_THREADS), 0, st, (float *)(e->ws + e->map.x),
+int hx_launch_embed_norm(const hx_engine *e, int batch, const int32_t *tokens, size_t gain_off, hipStream_t st, int blocks,
+                         size_t block_stride) {
+    hipLaunchKernelGGL((norm_kernel<0>), dim3(batch, blocks), dim3(HX_NORM_THREADS), 0, st, (float *)(e->ws + e->map.x),
                        (const float *)nullptr, tokens, (const uint16_t *)(e->weights + e->embed),
                        (const float *)nullptr, 0, (size_t)0, (const uint16_t *)(e->weights + gain_off), e->cfg.hidden,
-                       e->cfg.rms_eps, (uint16_t *)(e->ws + e->map.xp), hx_m_groups(batch), (float *)nullptr);
+                       e->cfg.rms_eps, (uint16_t *)(e->ws + e->map.xp), hx_m_groups(batch), (float *)nullptr, block_stride);
     HX_CHECK_LAUNCH("embed_norm");
     return HX_OK;
 }
 
 int hx_launch_reduce_norm(const hx_engine *e, int batch, const float *ypart, int splits, size_t split_stride,
-                          size_t gain_off, hipStream_t st) {
-    hipLaunchKernelGGL((norm_kernel<1>), dim3(batch), dim3(HX_NORM_THREADS), 0, st, (float *)(e->ws + e->map.x),
+                          size_t gain_off, hipStream_t st, int blocks, size_t block_stride) {
+    hipLaunchKernelGGL((norm_kernel<1>), dim3(batch, blocks), dim3(HX_NORM_THREADS), 0, st, (float *)(e->ws + e->map.x),
                        (const float *)nullptr, (const int32_t *)nullptr, (const uint16_t *)nullptr, ypart, splits,
                        split_stride, (const uint16_t *)(e->weights + gain_off), e->cfg.hidden, e->cfg.rms_eps,
-                       (uint16_t *)(e->ws + e->map.xp), hx_m_groups(batch), (float *)nullptr);
+                       (uint16_t *)(e->ws + e->map.xp), hx_m_groups(batch), (float *)nullptr, block_stride);
     HX_CHECK_LAUNCH("reduce_norm");
     return HX_OK;
 }
@@ -137,7 +145,7 @@ int hx_launch_norm_only(const hx_engine *e, int batch, const float *x, size_t ga
     hipLaunchKernelGGL((norm_kernel<2>), dim3(batch), dim3(HX_NORM_THREADS), 0, st, (float *)nullptr, x,
                        (const int32_t *)nullptr, (const uint16_t *)nullptr, (const float *)nullptr, 0, (size_t)0,
                        (const uint16_t *)(e->weights + gain_off), e->cfg.hidden, e->cfg.rms_eps, (uint16_t *)nullptr,
-                       hx_m_groups(batch), y);
+                       hx_m_groups(batch), y, (size_t)0);
     HX_CHECK_LAUNCH("norm_only");
     return HX_OK;
 }

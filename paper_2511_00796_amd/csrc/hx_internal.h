@@ -249,7 +249,8 @@ int hx_launch_kv_scatter(const hx_kv *kv, int layer, const void *k, const void *
                          const int32_t *table, int max_blocks, int batch, int64_t total_tokens, bool gather,
                          hipStream_t st);
 int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int batch, const float *ypart,
-                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st);
+                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st, int blocks = 1,
+                          size_t block_stride = 0);
 
 // attention.hip
 // bufs: NULL = the engine's workspace
@@ -294,7 +295,8 @@ int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_len
                           hipStream_t st);
 int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
                               hipStream_t st);
-int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st);
+int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st, int blocks = 1,
+                            size_t block_stride = 0);
 
 // attention_fp8.hip: the decode step's attention over an 8-bit cache
 int hx_launch_attention_fp8(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
@@ -306,14 +308,21 @@ int hx_launch_nucleus(const hx_engine *e, int batch, const float *logits, const 
 int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void *xp, int epilogue,
                    float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st,
                    const hx_sample_params *sample = nullptr);
+// gemm_wide.hip: products over several 256-row blocks at once (prompt rows)
+int hx_wide_splits(const hx_matrix *m, int row_blocks);
+int hx_launch_gemm_wide(const hx_engine *e, const hx_matrix *m, int row_blocks, char *ws0, size_t block_stride, size_t xp_off,
+                        int epilogue, size_t y_off, size_t mp_off, int splits, hipStream_t st);
+
 int hx_launch_sample_final(const hx_engine *e, int batch, int32_t *tokens_out, float *logprobs_out, hipStream_t st);
 int hx_gemm_splits(const hx_matrix *m, int batch);   // K-splits the planner uses for a product with split partials
 int hx_launch_argmax_final(const hx_engine *e, int batch, int32_t *tokens_out, hipStream_t st);
 
 // elementwise.hip
-int hx_launch_embed_norm(const hx_engine *e, int batch, const int32_t *tokens, size_t gain_off, hipStream_t st);
+// blocks > 1 (wide prompt calls): the same launch over further 256-row blocks whose workspaces follow at block_stride bytes
+int hx_launch_embed_norm(const hx_engine *e, int batch, const int32_t *tokens, size_t gain_off, hipStream_t st, int blocks = 1,
+                         size_t block_stride = 0);
 int hx_launch_reduce_norm(const hx_engine *e, int batch, const float *ypart, int splits, size_t split_stride,
-                          size_t gain_off, hipStream_t st);
+                          size_t gain_off, hipStream_t st, int blocks = 1, size_t block_stride = 0);
 int hx_launch_pack_x(const hx_engine *e, int batch, const float *x, int K, void *xp, hipStream_t st);
 int hx_launch_unpack_x(const hx_engine *e, int batch, const void *xp, int K, float *x, hipStream_t st);
 int hx_launch_unpack_q(const hx_engine *e, int batch, float *q_out, hipStream_t st);

@@ -122,10 +122,18 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
                                                           const int32_t *__restrict__ blk_new,
                                                           char *pool_layer, size_t block_bytes, size_t tile_bytes,
                                                           uint16_t *__restrict__ qp, int n_q, int n_kv, int G,
-                                                          int max_batch) {
+                                                          int max_batch, size_t block_stride) {
     constexpr int HALF = D / 2;
     constexpr int RPH = HALF / 8;                         // rotation items per head
     const int b = blockIdx.x;
+    if (blockIdx.z) {               // further row blocks of a wide prompt call: same layout, block_stride bytes apart
+        const size_t off = (size_t)blockIdx.z * block_stride;
+        ypart = (const float *)((const char *)ypart + off);
+        cs = (const float *)((const char *)cs + off);
+        blk_new = (const int32_t *)((const char *)blk_new + off);
+        qp = (uint16_t *)((char *)qp + off);
+        positions += (size_t)blockIdx.z * gridDim.x;
+    }
     const int item = blockIdx.y * blockDim.x + threadIdx.x;
     const int rot_items = (n_q + n_kv) * RPH;
     const int v_items = n_kv * (D / 16);
@@ -219,18 +227,19 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float *__restric
 }
 
 int hx_launch_rope_append(const hx_engine *e, const hx_kv *kv, int layer, int batch, const float *ypart,
-                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st) {
+                          int splits, size_t split_stride, const int32_t *positions, hipStream_t st, int blocks,
+                          size_t block_stride) {
     const hx_layer_map &lm = e->layers[layer];
     char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     const uint16_t *bias = (const uint16_t *)(e->weights + lm.bqkv);
     const float *cs = (const float *)(e->ws + e->map.cs);
     uint16_t *qp = (uint16_t *)(e->ws + e->map.qp);
     const int items = (e->cfg.n_q_heads + e->cfg.n_kv_heads) * (e->D / 16) + e->cfg.n_kv_heads * (e->D / 16);
-    dim3 grid(batch, (items + 127) / 128), block(128);
+    dim3 grid(batch, (items + 127) / 128, blocks), block(128);
 #define HX_ROPE_LAUNCH(DD, F8)                                                                                  \
     hipLaunchKernelGGL((rope_append_kernel<DD, F8>), grid, block, 0, st, ypart, splits, split_stride, bias,    \
                        e->cfg.qkv_bias, cs, positions, (const int32_t *)(e->ws + e->map.blk_new), pool_layer, kv->block_bytes, \
-                       kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch)
+                       kv->tile_bytes, qp, e->cfg.n_q_heads, e->cfg.n_kv_heads, e->G, e->cfg.max_batch, block_stride)
     if (e->D == 128) { if (kv->fp8) HX_ROPE_LAUNCH(128, true); else HX_ROPE_LAUNCH(128, false); }
     else             { if (kv->fp8) HX_ROPE_LAUNCH(64, true);  else HX_ROPE_LAUNCH(64, false); }
 #undef HX_ROPE_LAUNCH

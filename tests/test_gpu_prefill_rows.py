@@ -1,0 +1,158 @@
+"""prefill_rows: prompt rows in blocks of 256 with every matrix product taken over all rows of the call at once
+(the workgroup-tiled product of gemm_wide.hip instead of the weight-streaming one).
+
+Checks.  (1) Against the oracle: prompts totalling more than 1 024 rows go through ONE prefill_rows call (the rest
+through prefill_chunk), then one decode step; the last token's logits against the oracle's dense causal recomputation,
+at the contract bar.  Shapes chosen so that the products run with several K-splits, with an odd number of two-step
+chunks (the padded chunk) and with column blocks that end inside a workgroup's 256 columns.  (2) Against the library's
+own 256-row path: layer 0's cache entries are equal but for rare rounding flips (same inputs, another summation order),
+deeper layers' stay within a bf16 step on average.  (3) Argument errors are
+refused on the host."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_00796_amd import synth
+from util import host_model
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def hx():
+    from paper_2511_00796_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def build(hx, shape, seed, max_seq_len, kv_dtype=0):
+    eng = hx.Engine(shape, 256, max_seq_len, kv_dtype=kv_dtype)
+    for l in range(shape.n_layers):
+        eng.pack_layer(l, synth.layer_weights(shape, l, seed))
+    eng.pack_globals(synth.global_weights(shape, seed))
+    return eng
+
+
+def prompt_rows(ctx):
+    """(sequence, position) of every prompt token but the last of each sequence, sequence by sequence."""
+    return [(b, p) for b in range(len(ctx)) for p in range(int(ctx[b]) - 1)]
+
+
+def feed(hx, eng, kv, prompts, table, rows, wide_rows):
+    """The first `wide_rows` rows through one prefill_rows call, the others through prefill_chunk."""
+    def arrays(chunk):
+        bs = np.array([b for b, _ in chunk])
+        ps = np.array([p for _, p in chunk], dtype=np.int32)
+        toks = np.array([prompts[b][p] for b, p in chunk], dtype=np.int32)
+        return dev(toks), dev(ps), dev(ps + 1), dev(table[bs])
+    at = 0
+    if wide_rows:
+        ws = torch.empty(hx.prefill_workspace_bytes(eng.cfg, wide_rows), dtype=torch.uint8, device="cuda")
+        eng.prefill_rows(kv, *arrays(rows[:wide_rows]), ws)
+        at = wide_rows
+    while at < len(rows):
+        eng.prefill_chunk(kv, *arrays(rows[at:at + 256]))
+        at += 256
+
+
+SHAPES = {
+    # hidden 256 (16 k-steps), intermediate 704 (44 k-steps): no K-splits, 8 chunks / 22 chunks
+    "d64_g2": synth.ModelShape("rows-a", 2, 256, 4, 2, 64, 704, 1024),
+    # hidden 512, intermediate 2080 (130 k-steps = 65 chunks: odd, and enough for K-splits), 5 query heads per KV head;
+    # the QKV product has 896 columns = 3.5 column blocks
+    "d128_g5": synth.ModelShape("rows-b", 2, 512, 5, 1, 128, 2080, 1000),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SHAPES))
+def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name):
+    s = SHAPES[name]
+    seed = 123
+    ow, g, layers = host_model(s, seed)
+    cfg = oracle.make_config(s)
+    rng = np.random.default_rng(seed)
+    ctx = np.array([1100, 300, 37, 2], dtype=np.int32)
+    prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
+    table, nb = synth.block_table(ctx + 1, s.block_size, seed)
+    rows = prompt_rows(ctx)
+    wide = len(rows) // 256 * 256
+    assert wide >= 1024
+    eng = build(hx, s, seed, int(ctx.max()) + 1)
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    feed(hx, eng, kv, prompts, table, rows, wide)
+
+    # the same prompts through the 256-row path into a second cache: the two caches agree up to rounding flips
+    kv2 = hx.KVCache(eng, nb)
+    kv2.pool.fill_(0xFF)
+    feed(hx, eng, kv2, prompts, table, rows, 0)
+    torch.cuda.synchronize()
+    a = kv.pool.view(torch.bfloat16).float().view(s.n_layers, -1)
+    b2 = kv2.pool.view(torch.bfloat16).float().view(s.n_layers, -1)
+    written = torch.isfinite(b2)                       # 0xFFFF is a NaN pattern: never-written elements
+    assert torch.equal(written, torch.isfinite(a))
+    for l in range(s.n_layers):
+        x, y = a[l][written[l]], b2[l][written[l]]
+        diff = (x - y).abs()
+        frac = float((diff > 0).float().mean())
+        rel = float(diff.mean() / y.abs().mean())
+        worst = float(diff.max() / y.abs().max())
+        print("%s layer %d: caches of the two paths: %.3f %% of elements differ, mean |diff| / mean |value| %.2e" % (name, l, 100 * frac, rel))
+        if l == 0:
+            # same inputs, another summation order in the projection: a bf16 rounding flips on a rare element
+            # (by at most one bf16 step of the largest magnitude: a rotated value can be small against its two terms)
+            assert frac <= 1e-3 and worst <= 2.0 ** -7, (frac, worst)
+        else:
+            # deeper layers see the flips of the layers before (measured: a third of the elements one step apart, as
+            # between the oracle and its reordered evaluation); the comparison with the oracle below is the criterion
+            assert rel <= 1e-2, rel
+
+    # one decode step on the cache the wide call filled: the last token's logits against the oracle
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[b][-1] for b in range(len(ctx))], dtype=np.int32)
+    logits = torch.empty(len(ctx), s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(len(ctx), dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    assert np.isfinite(gl).all()
+    worst = 0.0
+    for b in range(len(ctx)):
+        ref = oracle.full_causal(cfg, ow, prompts[b])[0][-1]
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(gl[b] - ref).max())
+        assert err <= LOGIT_TOL * scale, (name, b, err, scale)
+        worst = max(worst, err / scale)
+    print("%s: %d rows in one prefill_rows call: worst logit err / max|logit| %.3e" % (name, wide, worst))
+
+
+def test_argument_errors_are_refused_on_the_host(hx):
+    s = SHAPES["d64_g2"]
+    eng = build(hx, s, 5, 600)
+    kv = hx.KVCache(eng, 64)
+    z = torch.zeros(512, dtype=torch.int32, device="cuda")
+    table = torch.zeros(512, 4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(hx.prefill_workspace_bytes(eng.cfg, 512), dtype=torch.uint8, device="cuda")
+    with pytest.raises(hx.HexError):                   # not a multiple of 256
+        eng.prefill_rows(kv, z[:300], z[:300], z[:300], table[:300], ws)
+    with pytest.raises(hx.HexError):                   # workspace for 256 rows, 512 asked
+        eng.prefill_rows(kv, z, z, z, table, ws[:ws.numel() // 2])
+    with pytest.raises(hx.HexError):
+        hx.prefill_workspace_bytes(eng.cfg, 100)
+    small = hx.Engine(s, 64, 600)
+    with pytest.raises(hx.HexError):                   # engine not created for 256 rows
+        hx.prefill_workspace_bytes(small.cfg, 256)
+    odd = synth.ModelShape("rows-odd", 2, 256, 4, 2, 64, 688, 1024)      # intermediate 688 is not a multiple of 32
+    eng_odd = hx.Engine(odd, 256, 600)
+    kv_odd = hx.KVCache(eng_odd, 64)
+    ws_odd = torch.empty(hx.prefill_workspace_bytes(eng_odd.cfg, 256), dtype=torch.uint8, device="cuda")
+    with pytest.raises(hx.HexError):
+        eng_odd.prefill_rows(kv_odd, z[:256], z[:256], z[:256], table[:256], ws_odd)
