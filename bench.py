@@ -204,7 +204,7 @@ def main():
         n_streams = args.prefill_streams
         # further engines share the packed weights; each has its own workspace, cache and stream
         lanes = [(eng, kvc, torch.cuda.current_stream())]
-        for _ in range(1, n_streams):
+        for _ in range(1, 1 if args.prefill_rows_per_call > 256 else n_streams):
             e2 = binding.Engine(s, R, P + 1, kv_dtype=kvd, weights=eng.weights)
             k2 = binding.KVCache(e2, nb)
             k2.pool.zero_()
@@ -212,21 +212,31 @@ def main():
         if args.prefill_rows_per_call > 256:
             # M consecutive positions of one prompt per call, through prefill_rows
             M = args.prefill_rows_per_call
-            assert M % 256 == 0 and P % M == 0 and n_streams == 1
+            assert M % 256 == 0 and P % M == 0
             table_d = torch.from_numpy(table).cuda()
             toks = torch.randint(0, s.vocab, (M,), dtype=torch.int32, device="cuda")
             pos_of_call = [torch.arange(M, dtype=torch.int32, device="cuda") + c * M for c in range(P // M)]
             len_of_call = [p + 1 for p in pos_of_call]
-            wide_ws = torch.empty(binding.prefill_workspace_bytes(eng.cfg, M), dtype=torch.uint8, device="cuda")
+            # calls on different streams share the engine (weights, layouts) and differ in workspace and cache
+            wide_lanes = []
+            for i in range(n_streams):
+                kv_i = kvc if i == 0 else binding.KVCache(eng, nb)
+                kv_i.pool.zero_()
+                st_i = torch.cuda.current_stream() if i == 0 else torch.cuda.Stream()
+                wide_lanes.append((kv_i, st_i, torch.empty(binding.prefill_workspace_bytes(eng.cfg, M), dtype=torch.uint8, device="cuda")))
+            wide_ws = wide_lanes[0][2]
             n_seq = min(B, 32)                                    # 32 prompts are enough for a steady figure
+            assert n_seq % n_streams == 0
             rows_of_seq = [table_d[g:g + 1].expand(M, -1).contiguous() for g in range(n_seq)]
             calls = n_seq * (P // M)
             torch.cuda.synchronize()
 
             def run_wide():
-                for g in range(n_seq):
+                for g in range(0, n_seq, n_streams):
                     for c in range(P // M):
-                        eng.prefill_rows(kvc, toks, pos_of_call[c], len_of_call[c], rows_of_seq[g], wide_ws)
+                        for i, (kv_i, st_i, ws_i) in enumerate(wide_lanes):
+                            with torch.cuda.stream(st_i):
+                                eng.prefill_rows(kv_i, toks, pos_of_call[c], len_of_call[c], rows_of_seq[g + i], ws_i)
 
             run_wide()
             torch.cuda.synchronize()
@@ -247,7 +257,7 @@ def main():
                               "value": M * calls / dt, "unit": "tokens/s", "n_gpus": 1, "seconds": dt, "calls": calls,
                               "rows_per_call": M, "ms_per_call": dt / calls * 1e3,
                               "config": {"workload": "%s-prefill" % s.name, "prompts": n_seq, "prompt_len": P, "rows_per_call": M,
-                                         "kv_cache": "fp8-e4m3" if args.kv_dtype == "fp8" else "bf16"},
+                                         "streams": n_streams, "kv_cache": "fp8-e4m3" if args.kv_dtype == "fp8" else "bf16"},
                               "data": "synthetic", "dtype": "bf16",
                               "product_flops_over_call_time_TFLOPs": call_flops / (dt / calls) / 1e12,
                               "roofline": {"kernel": "gemm_wide_kernel (gate|up product over all rows of the call)", "bound": "mfma",

@@ -134,6 +134,41 @@ def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name
     print("%s: %d rows in one prefill_rows call: worst logit err / max|logit| %.3e" % (name, wide, worst))
 
 
+def test_two_calls_on_two_streams_share_one_engine(hx):
+    """prefill_rows keeps its state in the workspace it is given: two calls on two streams, each with its own workspace
+    and cache, through ONE engine leave exactly the caches the same calls leave when run one after the other."""
+    s = SHAPES["d64_g2"]
+    seed = 77
+    eng = build(hx, s, seed, 600)
+    rng = np.random.default_rng(seed)
+    ctx = np.array([513, 513], dtype=np.int32)
+    prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
+    table, nb = synth.block_table(ctx + 1, s.block_size, seed)
+    args = []
+    for b in range(2):
+        ps = np.arange(512, dtype=np.int32)
+        args.append((dev(prompts[b][:512]), dev(ps), dev(ps + 1), dev(np.repeat(table[b:b + 1], 512, axis=0))))
+    nbytes = hx.prefill_workspace_bytes(eng.cfg, 512)
+
+    def run(concurrent):
+        kvs = [hx.KVCache(eng, nb) for _ in range(2)]
+        wss = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        for kv in kvs:
+            kv.pool.fill_(0xFF)
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()] if concurrent else [torch.cuda.current_stream()] * 2
+        for rep in range(3):                            # several calls in flight per stream
+            for b in range(2):
+                with torch.cuda.stream(streams[b]):
+                    eng.prefill_rows(kvs[b], *args[b], wss[b])
+        torch.cuda.synchronize()
+        return [kv.pool.clone() for kv in kvs]
+
+    alone, together = run(False), run(True)
+    for b in range(2):
+        assert torch.equal(alone[b], together[b])
+
+
 def test_argument_errors_are_refused_on_the_host(hx):
     s = SHAPES["d64_g2"]
     eng = build(hx, s, 5, 600)
