@@ -540,8 +540,8 @@ extern "C" int prefill_rows(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32
     auto table = [&](int b) { return block_table + (size_t)b * 256 * max_blocks; };
     const bool chunked = e->chunk_attention;
 
-    // The schedules are per block (one small launch each); the row kernels take all blocks in one launch (their
-    // block dimension strides through the workspaces), as do the products; the attention runs block by block.
+    // The schedules are per block (one small launch each); the row kernels and the grouped attention take all blocks in
+    // one launch (their block dimension strides through the workspaces), as do the products.
     const hx_engine *v0 = &view[0];
     const float *ypart0 = (const float *)(ws0 + m.ypart);
     for (int b = 0; b < R; ++b) {
@@ -558,11 +558,12 @@ extern "C" int prefill_rows(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32
         HX_TIMED(HX_K_ROPE, hx_launch_rope_append(v0, kv, l, 256, ypart0, s_qkv, (size_t)256 * e->qkv_dim, positions, st, R, stride));
         if (l + 1 == c->n_layers) break;     // of the last layer only its K and V are needed
         float *capture = e->attn_capture ? e->attn_capture + l * attn_stride : nullptr;
-        for (int b = 0; b < R; ++b) {
-            const hx_engine *vb = &view[b];
-            if (chunked) {
-                HX_TIMED(HX_K_ATTENTION, hx_launch_chunk_attention(vb, kv, l, table(b), max_blocks, st));
-            } else {
+        if (chunked) {
+            // one launch over all blocks: each block has its own schedule; the wavefronts beyond a block's runs exit
+            HX_TIMED(HX_K_ATTENTION, hx_launch_chunk_attention(v0, kv, l, block_table, max_blocks, st, R, stride, 256));
+        } else {
+            for (int b = 0; b < R; ++b) {
+                const hx_engine *vb = &view[b];
                 if (kv->fp8) HX_TIMED(HX_K_ATTENTION, hx_launch_attention_fp8(vb, kv, l, table(b), max_blocks, st));
                 else HX_TIMED(HX_K_ATTENTION, hx_launch_attention(vb, kv, l, 256, rows(seq_lens, b), table(b), max_blocks, st));
                 HX_TIMED(HX_K_COMBINE, hx_launch_combine(vb, 256, capture ? capture + (size_t)b * 256 * e->q_dim : nullptr, st));

@@ -274,11 +274,23 @@ __global__ __launch_bounds__(64, 2) void attn_chunk_kernel(const char *__restric
                                                         const int32_t *__restrict__ sched,
                                                         const int32_t *__restrict__ ginfo, int n_kv, int G,
                                                         float scale_log2e, float *__restrict__ part_ml,
-                                                        float *__restrict__ part_o) {
+                                                        float *__restrict__ part_o, size_t block_stride,
+                                                        size_t table_block_stride) {
     // query operands of the 4 column blocks; every lane reads back only what it wrote itself
     __shared__ u32x4_t qs[HX_CHUNK_CB * (D / 32) * 64];
     const int w = blockIdx.x;
     const int lane = threadIdx.x;
+    if (blockIdx.y) {               // further row blocks of a wide prompt call: each with its own schedule, queries and
+        const size_t off = (size_t)blockIdx.y * block_stride;      // partial results, block_stride bytes apart
+        qp = (const uint16_t *)((const char *)qp + off);
+        pre = (const int32_t *)((const char *)pre + off);
+        lens = (const int32_t *)((const char *)lens + off);
+        sched = (const int32_t *)((const char *)sched + off);
+        ginfo = (const int32_t *)((const char *)ginfo + off);
+        part_ml = (float *)((char *)part_ml + off);
+        part_o = (float *)((char *)part_o + off);
+        table += (size_t)blockIdx.y * table_block_stride;
+    }
     const int S = sched[0], Nt = sched[1];
     int f = w * S;
     const int f1 = min(Nt, f + S);
@@ -464,16 +476,17 @@ int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_len
 }
 
 int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
-                              hipStream_t st) {
+                              hipStream_t st, int blocks, size_t block_stride, int rows_per_block) {
     const char *pool_layer = kv->pool + (size_t)layer * kv->layer_bytes;
     char *ws = e->ws;
     const float scale_log2e = (float)(1.4426950408889634 / sqrt((double)e->D));
-    dim3 grid(e->attn_waves), block(64);
+    dim3 grid(e->attn_waves, blocks), block(64);
 #define HX_CHUNK_ARGS                                                                                            \
     pool_layer, kv->block_bytes, (const uint16_t *)(ws + e->map.qp), table, max_blocks,                          \
         (const int32_t *)(ws + e->map.pre), (const int32_t *)(ws + e->map.lens),                                 \
         (const int32_t *)(ws + e->map.sched), (const int32_t *)(ws + e->map.chunk_ginfo), e->cfg.n_kv_heads,     \
-        e->G, scale_log2e, (float *)(ws + e->map.chunk_part_ml), (float *)(ws + e->map.chunk_part_o)
+        e->G, scale_log2e, (float *)(ws + e->map.chunk_part_ml), (float *)(ws + e->map.chunk_part_o), block_stride,   \
+        (size_t)rows_per_block * max_blocks
     if (kv->fp8) {
         if (e->D == 128) hipLaunchKernelGGL((attn_chunk_kernel<128, 2, true>), grid, block, 0, st, HX_CHUNK_ARGS);
         else             hipLaunchKernelGGL((attn_chunk_kernel<64, 3, true>), grid, block, 0, st, HX_CHUNK_ARGS);

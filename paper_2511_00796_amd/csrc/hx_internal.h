@@ -294,7 +294,7 @@ __device__ __forceinline__ void hx_philox4x32_10(uint32_t c0, uint32_t c1, uint3
 int hx_launch_chunk_setup(const hx_engine *e, int n_rows, const int32_t *seq_lens, const int32_t *table, int max_blocks,
                           hipStream_t st);
 int hx_launch_chunk_attention(const hx_engine *e, const hx_kv *kv, int layer, const int32_t *table, int max_blocks,
-                              hipStream_t st);
+                              hipStream_t st, int blocks = 1, size_t block_stride = 0, int rows_per_block = 0);
 int hx_launch_chunk_combine(const hx_engine *e, int n_rows, float *attn_f32_out, hipStream_t st, int blocks = 1,
                             size_t block_stride = 0);
 
