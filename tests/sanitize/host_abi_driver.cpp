@@ -85,9 +85,22 @@ int main() {
                 for (int batch : {1, 33, 64, 128, 256}) {
                     int32_t wn = 0, wk = 0, sp = 0;
                     EXPECT(hx_plan_product((p[1] + 31) / 32, p[0] / 16, batch, p[2], &wn, &wk, &sp) == HX_OK);
-                    EXPECT(wn >= 4 && wn <= 6 && wk >= 1 && sp >= 1 && sp <= 9 && (p[2] || sp == 1));
+                    EXPECT(((wn >= 4 && wn <= 6) || (wn == 10 && !p[2] && batch <= 128)) && wk >= 1 && sp >= 1 && sp <= 9 && (p[2] || sp == 1));
                 }
         }
+    }
+    {   // prompt-row workspace sizing: only for engines of 256 rows, multiples of 256 up to the limit
+        hx_model_config c256 = shapes[0];
+        c256.max_batch = 256;
+        size_t one = 0, four = 0;
+        EXPECT(hx_prefill_workspace_bytes(&c256, 256, &one) == HX_OK && one > 0);
+        EXPECT(hx_prefill_workspace_bytes(&c256, 1024, &four) == HX_OK && four == 4 * one);
+        EXPECT(hx_prefill_workspace_bytes(&c256, 300, &one) == HX_E_RANGE);
+        EXPECT(hx_prefill_workspace_bytes(&c256, HX_PREFILL_MAX_ROWS + 256, &one) == HX_E_RANGE);
+        EXPECT(hx_prefill_workspace_bytes(&c256, 256, nullptr) == HX_E_NULL);
+        hx_model_config c64 = shapes[0];
+        c64.max_batch = 64;
+        EXPECT(hx_prefill_workspace_bytes(&c64, 256, &one) == HX_E_RANGE);
     }
     hx_model_config bad = shapes[0];
     bad.head_dim = 96;

@@ -72,8 +72,11 @@ SHAPES = {
 }
 
 
+@pytest.mark.parametrize("wide_blocks", [1, 5])
 @pytest.mark.parametrize("name", sorted(SHAPES))
-def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name):
+def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name, wide_blocks):
+    """wide_blocks = 5: 1 280 rows in one call; 1: a single block of 256 rows (the products then run with more K-splits),
+    the other rows through prefill_chunk."""
     s = SHAPES[name]
     seed = 123
     ow, g, layers = host_model(s, seed)
@@ -83,8 +86,8 @@ def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name
     prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
     table, nb = synth.block_table(ctx + 1, s.block_size, seed)
     rows = prompt_rows(ctx)
-    wide = len(rows) // 256 * 256
-    assert wide >= 1024
+    assert len(rows) // 256 == 5
+    wide = wide_blocks * 256
     eng = build(hx, s, seed, int(ctx.max()) + 1)
     kv = hx.KVCache(eng, nb)
     kv.pool.fill_(0xFF)
