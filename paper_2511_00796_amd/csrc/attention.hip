@@ -328,42 +328,59 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(int batch, int n_q, i
     const int start = pre[b] * n_kv + kvh * nblk_b;      // tiles of this pair: [start, start + nblk_b)
     const int pair = b * n_kv + kvh;
     const int s0 = start / S + pair, s1 = (start + nblk_b - 1) / S + pair;   // its slots, inclusive
-    // Maximum and denominator: one partial per lane, 64 at a time (a short batch of long sequences has a hundred
-    // partials per pair).  The weighted sum of the o vectors takes four partials per 16-lane group and iteration, all
-    // requested before the first is used.
+    // More than 8 partials per pair (a short batch of long sequences has a hundred): maximum and denominator take one
+    // partial per lane, 64 at a time; the weighted sum of the o vectors four partials per 16-lane group and iteration,
+    // all requested before the first is used.
     const int n = s1 - s0 + 1;
-    float M = HX_NEG_BIG;
-    for (int i = lane; i < n; i += 64) M = fmaxf(M, part_ml[(size_t)(s0 + i) * 32 + g]);
-#pragma unroll
-    for (int sh = 1; sh < 64; sh <<= 1) M = fmaxf(M, __shfl_xor(M, sh));
-    float den = 0.f;
-    for (int i = lane; i < n; i += 64) {
-        const float *ml = part_ml + (size_t)(s0 + i) * 32;
-        den += __builtin_amdgcn_exp2f(ml[g] - M) * ml[16 + g];
-    }
-#pragma unroll
-    for (int sh = 1; sh < 64; sh <<= 1) den += __shfl_xor(den, sh);
+    float M = HX_NEG_BIG, den = 0.f;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    for (int it = s0 + ph; it <= s1; it += 16) {
-        float w[4];
-        f32x4_t a[4], c[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int iu = min(it + 4 * u, s1);                       // past the end: re-read the last, weight 0
-            w[u] = part_ml[(size_t)iu * 32 + g];
+    if (n <= 8) {                   // the usual case (a few partials per pair): each 16-lane group takes every fourth
+        for (int it = s0 + ph; it <= s1; it += 4) M = fmaxf(M, part_ml[(size_t)it * 32 + g]);
+        M = fmaxf(M, __shfl_xor(M, 16));
+        M = fmaxf(M, __shfl_xor(M, 32));
+        for (int it = s0 + ph; it <= s1; it += 4) {
+            const float w = __builtin_amdgcn_exp2f(part_ml[(size_t)it * 32 + g] - M);
+            den += w * part_ml[(size_t)it * 32 + 16 + g];
             if (has_d) {
-                const float *po = part_o + ((size_t)iu * G + g) * D + d8 * 8;
-                a[u] = *(const f32x4_t *)po; c[u] = *(const f32x4_t *)(po + 4);
+                const float *po = part_o + ((size_t)it * G + g) * D + d8 * 8;
+                const f32x4_t a = *(const f32x4_t *)po, c = *(const f32x4_t *)(po + 4);
+                acc[0] += w * a[0]; acc[1] += w * a[1]; acc[2] += w * a[2]; acc[3] += w * a[3];
+                acc[4] += w * c[0]; acc[5] += w * c[1]; acc[6] += w * c[2]; acc[7] += w * c[3];
             }
         }
+        den += __shfl_xor(den, 16);
+        den += __shfl_xor(den, 32);
+    } else {
+        for (int i = lane; i < n; i += 64) M = fmaxf(M, part_ml[(size_t)(s0 + i) * 32 + g]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float wu = it + 4 * u <= s1 ? __builtin_amdgcn_exp2f(w[u] - M) : 0.f;
-            if (has_d) {
-                acc[0] += wu * a[u][0]; acc[1] += wu * a[u][1]; acc[2] += wu * a[u][2]; acc[3] += wu * a[u][3];
-                acc[4] += wu * c[u][0]; acc[5] += wu * c[u][1]; acc[6] += wu * c[u][2]; acc[7] += wu * c[u][3];
+        for (int sh = 1; sh < 64; sh <<= 1) M = fmaxf(M, __shfl_xor(M, sh));
+        for (int i = lane; i < n; i += 64) {
+            const float *ml = part_ml + (size_t)(s0 + i) * 32;
+            den += __builtin_amdgcn_exp2f(ml[g] - M) * ml[16 + g];
+        }
+#pragma unroll
+        for (int sh = 1; sh < 64; sh <<= 1) den += __shfl_xor(den, sh);
+        for (int it = s0 + ph; it <= s1; it += 16) {
+            float w[4];
+            f32x4_t a[4], c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int iu = min(it + 4 * u, s1);                   // past the end: re-read the last, weight 0
+                w[u] = part_ml[(size_t)iu * 32 + g];
+                if (has_d) {
+                    const float *po = part_o + ((size_t)iu * G + g) * D + d8 * 8;
+                    a[u] = *(const f32x4_t *)po; c[u] = *(const f32x4_t *)(po + 4);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wu = it + 4 * u <= s1 ? __builtin_amdgcn_exp2f(w[u] - M) : 0.f;
+                if (has_d) {
+                    acc[0] += wu * a[u][0]; acc[1] += wu * a[u][1]; acc[2] += wu * a[u][2]; acc[3] += wu * a[u][3];
+                    acc[4] += wu * c[u][0]; acc[5] += wu * c[u][1]; acc[6] += wu * c[u][2]; acc[7] += wu * c[u][3];
+                }
             }
         }
     }
