@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # HBM bytes per attention launch at workload 7b-b128 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain
 # copy (profiles/attn_splitk_7b-b128_hbm_traffic.txt).  Valid only for the kernel source they were taken with.
 PMC_TRAFFIC = {"workload": "7b-b128",
-               "attention_hip_sha256": "ce4a52c28c312d334b4bb9ebe9e124dfd7ff3c1070d172ffbd8306e7bb746209",
-               "fetch_bytes": 2165.72e6, "write_bytes": 9.45e6}
+               "attention_hip_sha256": "11c5439d0fe03dfc65f9e7571695422881c8be675a5bff743dad012a6a914306",
+               "fetch_bytes": 2165.63e6, "write_bytes": 9.45e6}
 
 
 def measured_traffic(workload_name):
