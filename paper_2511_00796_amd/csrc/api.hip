@@ -552,8 +552,10 @@ extern "C" int prefill_rows(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32
     HX_TIMED(HX_K_NORM, hx_launch_embed_norm(v0, 256, tokens, e->layers[0].g1, st, R, stride));
     for (int l = 0; l < c->n_layers; ++l) {
         const hx_layer_map *lm = &e->layers[l];
-        const int s_qkv = hx_wide_splits(&lm->wqkv, R), s_o = hx_wide_splits(&lm->wo, R), s_d = hx_wide_splits(&lm->wd, R);
-        HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm_wide(e, &lm->wqkv, R, ws0, stride, m.xp, HX_EPI_PARTIAL, m.ypart, 0, s_qkv, st));
+        const hx_wide_plan p_qkv = hx_plan_wide(&lm->wqkv, R, true), p_o = hx_plan_wide(&lm->wo, R, true),
+                           p_gu = hx_plan_wide(&lm->wgu, R, false), p_d = hx_plan_wide(&lm->wd, R, true);
+        const int s_qkv = p_qkv.splits, s_o = p_o.splits, s_d = p_d.splits;
+        HX_TIMED(HX_K_GEMM_QKV, hx_launch_gemm_wide(e, &lm->wqkv, R, ws0, stride, m.xp, HX_EPI_PARTIAL, m.ypart, 0, p_qkv, st));
         // K and V of every row of the call enter the cache before any row attends
         HX_TIMED(HX_K_ROPE, hx_launch_rope_append(v0, kv, l, 256, ypart0, s_qkv, (size_t)256 * e->qkv_dim, positions, st, R, stride));
         if (l + 1 == c->n_layers) break;     // of the last layer only its K and V are needed
@@ -570,10 +572,10 @@ extern "C" int prefill_rows(hx_engine *e, hx_kv *kv, int32_t n_rows, const int32
             }
         }
         if (chunked) HX_TIMED(HX_K_COMBINE, hx_launch_chunk_combine(v0, 256, capture, st, R, stride));
-        HX_TIMED(HX_K_GEMM_O, hx_launch_gemm_wide(e, &lm->wo, R, ws0, stride, m.ap, HX_EPI_PARTIAL, m.ypart, 0, s_o, st));
+        HX_TIMED(HX_K_GEMM_O, hx_launch_gemm_wide(e, &lm->wo, R, ws0, stride, m.ap, HX_EPI_PARTIAL, m.ypart, 0, p_o, st));
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(v0, 256, ypart0, s_o, (size_t)256 * c->hidden, lm->g2, st, R, stride));
-        HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm_wide(e, &lm->wgu, R, ws0, stride, m.xp, HX_EPI_SWIGLU, 0, m.mp, 1, st));
-        HX_TIMED(HX_K_GEMM_DOWN, hx_launch_gemm_wide(e, &lm->wd, R, ws0, stride, m.mp, HX_EPI_PARTIAL, m.ypart, 0, s_d, st));
+        HX_TIMED(HX_K_GEMM_GATE_UP, hx_launch_gemm_wide(e, &lm->wgu, R, ws0, stride, m.xp, HX_EPI_SWIGLU, 0, m.mp, p_gu, st));
+        HX_TIMED(HX_K_GEMM_DOWN, hx_launch_gemm_wide(e, &lm->wd, R, ws0, stride, m.mp, HX_EPI_PARTIAL, m.ypart, 0, p_d, st));
         const size_t next_gain = (l + 1 < c->n_layers) ? e->layers[l + 1].g1 : e->gf;
         HX_TIMED(HX_K_NORM, hx_launch_reduce_norm(v0, 256, ypart0, s_d, (size_t)256 * c->hidden, next_gain, st, R, stride));
     }

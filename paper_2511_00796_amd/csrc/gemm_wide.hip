@@ -28,9 +28,8 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int WIDE_WNT = 8;       // 32-column tiles per workgroup (256 columns)
 constexpr int WIDE_KC = 2;        // k-steps per chunk
-constexpr int WIDE_LDS_BYTES = 2 * WIDE_KC * (8 + WIDE_WNT) * 1024;
+constexpr int wide_lds_bytes(int wnt) { return 2 * WIDE_KC * (8 + wnt) * 1024; }
 
 #define HX_WIDE_LGKM0 0xC07F      /* s_waitcnt lgkmcnt(0) and nothing else */
 
@@ -45,9 +44,11 @@ struct WideArgs {
     uint16_t *mp0;                // SiLU(gate)*up output of block 0 (packed activations, 8 m-groups)
 };
 
-template <int EPI, bool TAIL>
+// WNT: 32-column tiles per workgroup: 8 (a 256 x 256 output tile) or 6 (256 x 192, for products that would otherwise
+// leave compute units idle)
+template <int WNT, int EPI, bool TAIL>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(WideArgs a) {
-    constexpr int WNT = WIDE_WNT, KC = WIDE_KC, TW = WNT / 2, PIECES = KC * (8 + WNT), LPW = PIECES / 4, STAGE_U4 = PIECES * 64;
+    constexpr int KC = WIDE_KC, TW = WNT / 2, PIECES = KC * (8 + WNT), LPW = PIECES / 4, STAGE_U4 = PIECES * 64;
     extern __shared__ u32x4_t lds[];                    // [2 stages][PIECES][64 lanes]
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int w = blockIdx.x, xcd = w & 7, slot = w >> 3;
@@ -215,36 +216,45 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(WideArgs a) {
     }
 }
 
-template <int EPI, bool TAIL>
+template <int WNT, int EPI, bool TAIL>
 int launch_wide(dim3 grid, hipStream_t st, const WideArgs &a) {
     static std::once_flag once;
     static hipError_t configured = hipSuccess;
     std::call_once(once, [] {
-        configured = hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, TAIL>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         WIDE_LDS_BYTES);
+        configured = hipFuncSetAttribute((const void *)gemm_wide_kernel<WNT, EPI, TAIL>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         wide_lds_bytes(WNT));
     });
     if (configured != hipSuccess) return hx_fail(HX_E_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(configured));
-    hipLaunchKernelGGL((gemm_wide_kernel<EPI, TAIL>), grid, dim3(256), WIDE_LDS_BYTES, st, a);
+    hipLaunchKernelGGL((gemm_wide_kernel<WNT, EPI, TAIL>), grid, dim3(256), wide_lds_bytes(WNT), st, a);
     return HX_OK;
+}
+
+template <int WNT>
+int launch_wide_epi(int epilogue, bool tail, dim3 grid, hipStream_t st, const WideArgs &a) {
+    if (epilogue == HX_EPI_PARTIAL) return tail ? launch_wide<WNT, HX_EPI_PARTIAL, true>(grid, st, a) : launch_wide<WNT, HX_EPI_PARTIAL, false>(grid, st, a);
+    return tail ? launch_wide<WNT, HX_EPI_SWIGLU, true>(grid, st, a) : launch_wide<WNT, HX_EPI_SWIGLU, false>(grid, st, a);
 }
 
 }  // namespace
 
-// K-splits of a wide product whose consumer sums partials: enough workgroups for the device, whole chunks per split.
-int hx_wide_splits(const hx_matrix *m, int row_blocks) {
+// Tiles per workgroup and, for a product whose consumer sums partials, K-splits: the time of the busiest compute unit
+// (rounds x tiles per workgroup x k-steps per split), with a charge per extra split for writing and re-reading its
+// partial (measured: a 256 x N fp32 partial per row block is about 4 % of a 3584-deep product) and one per narrower
+// tile (it draws more bytes per flop).  Splits hold whole chunks.
+hx_wide_plan hx_plan_wide(const hx_matrix *m, int row_blocks, bool partial) {
     const int cus = hx_device_cus();
-    const int NB = (m->n_tiles + WIDE_WNT - 1) / WIDE_WNT;
-    int best = 1;
+    hx_wide_plan best{8, 1};
     double best_cost = 1e300;
-    for (int s = 1; s <= HX_MAX_SPLITS; ++s) {
-        if (s > 1 && m->k_steps / s < 32) break;
-        const int wgs = NB * row_blocks * s;
-        const int rounds = (wgs + cus - 1) / cus;
-        const int sps = ((m->k_steps + s - 1) / s + 1) & ~1;
-        // time of the busiest compute unit, plus what writing and re-reading one more partial costs (measured:
-        // a 256 x N fp32 partial per row block is about 2 % of a 3584-deep product)
-        const double cost = (double)rounds * sps * (1.0 + 0.04 * (s - 1));
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+    for (int wnt : {8, 6}) {
+        const int NB = (m->n_tiles + wnt - 1) / wnt;
+        for (int s = 1; s <= (partial ? HX_MAX_SPLITS : 1); ++s) {
+            if (s > 1 && m->k_steps / s < 32) break;
+            const int wgs = NB * row_blocks * s;
+            const int rounds = (wgs + cus - 1) / cus;
+            const int sps = ((m->k_steps + s - 1) / s + 1) & ~1;
+            const double cost = (double)rounds * wnt * sps * (1.0 + 0.04 * (s - 1)) * (1.0 + 0.03 * (8 - wnt));
+            if (cost < best_cost - 1e-9) { best_cost = cost; best.wnt = wnt; best.splits = s; }
+        }
     }
     return best;
 }
@@ -253,7 +263,10 @@ int hx_wide_splits(const hx_matrix *m, int row_blocks) {
 // the fp32 output ([splits][256][N]) and the SiLU*mul output inside each block's workspace; ws0 = block 0's
 // workspace, block_stride bytes between blocks.
 int hx_launch_gemm_wide(const hx_engine *e, const hx_matrix *m, int row_blocks, char *ws0, size_t block_stride, size_t xp_off,
-                        int epilogue, size_t y_off, size_t mp_off, int splits, hipStream_t st) {
+                        int epilogue, size_t y_off, size_t mp_off, hx_wide_plan plan, hipStream_t st) {
+    int splits = plan.splits;
+    const int wnt = plan.wnt;
+    if (wnt != 8 && wnt != 6) return hx_fail(HX_E_RANGE, "%d tiles per workgroup: no such wide product", wnt);
     if (m->k_steps % WIDE_KC) return hx_fail(HX_E_SHAPE, "wide products need K to be a multiple of 32, not %d", m->k_steps * 16);
     if (epilogue != HX_EPI_PARTIAL && epilogue != HX_EPI_SWIGLU) return hx_fail(HX_E_RANGE, "epilogue %d has no wide product", epilogue);
     if (epilogue == HX_EPI_SWIGLU) splits = 1;
@@ -265,7 +278,7 @@ int hx_launch_gemm_wide(const hx_engine *e, const hx_matrix *m, int row_blocks, 
     a.y0 = (float *)(ws0 + y_off);
     a.mp0 = (uint16_t *)(ws0 + mp_off);
     a.steps_per_split = ((m->k_steps + splits - 1) / splits + 1) & ~1;
-    const int NB = (m->n_tiles + WIDE_WNT - 1) / WIDE_WNT;
+    const int NB = (m->n_tiles + wnt - 1) / wnt;
     dim3 grid(((NB + 7) / 8) * 8 * row_blocks, splits);
     bool tail = false;                                  // some split has an odd number of chunks
     for (int s = 0; s < splits; ++s) {
@@ -273,9 +286,7 @@ int hx_launch_gemm_wide(const hx_engine *e, const hx_matrix *m, int row_blocks, 
         if (k1 <= k0) return hx_fail(HX_E_RANGE, "%d splits leave split %d of %d k-steps empty", splits, s, m->k_steps);
         if (((k1 - k0) / WIDE_KC) & 1) tail = true;
     }
-    int rc;
-    if (epilogue == HX_EPI_PARTIAL) rc = tail ? launch_wide<HX_EPI_PARTIAL, true>(grid, st, a) : launch_wide<HX_EPI_PARTIAL, false>(grid, st, a);
-    else rc = tail ? launch_wide<HX_EPI_SWIGLU, true>(grid, st, a) : launch_wide<HX_EPI_SWIGLU, false>(grid, st, a);
+    const int rc = wnt == 8 ? launch_wide_epi<8>(epilogue, tail, grid, st, a) : launch_wide_epi<6>(epilogue, tail, grid, st, a);
     if (rc) return rc;
     HX_CHECK_LAUNCH("gemm_wide");
     return HX_OK;

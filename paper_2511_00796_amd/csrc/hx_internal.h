@@ -309,9 +309,10 @@ int hx_launch_gemm(const hx_engine *e, const hx_matrix *m, int batch, const void
                    float *y /*partials or logits or NULL*/, void *mp_out, hipStream_t st,
                    const hx_sample_params *sample = nullptr);
 // gemm_wide.hip: products over several 256-row blocks at once (prompt rows)
-int hx_wide_splits(const hx_matrix *m, int row_blocks);
+struct hx_wide_plan { int wnt, splits; };        // 32-column tiles per workgroup, K-splits
+hx_wide_plan hx_plan_wide(const hx_matrix *m, int row_blocks, bool partial);
 int hx_launch_gemm_wide(const hx_engine *e, const hx_matrix *m, int row_blocks, char *ws0, size_t block_stride, size_t xp_off,
-                        int epilogue, size_t y_off, size_t mp_off, int splits, hipStream_t st);
+                        int epilogue, size_t y_off, size_t mp_off, hx_wide_plan plan, hipStream_t st);
 
 int hx_launch_sample_final(const hx_engine *e, int batch, int32_t *tokens_out, float *logprobs_out, hipStream_t st);
 int hx_gemm_splits(const hx_matrix *m, int batch);   // K-splits the planner uses for a product with split partials
