@@ -327,6 +327,12 @@ int hx_stage_rmsnorm(hx_engine *engine, int gain_kind, int layer, int32_t batch,
 int hx_stage_linear(hx_engine *engine, int matrix_kind, int layer, int32_t batch, const float *x_dev,
                     float *y_dev, int32_t *argmax_out_dev, void *stream);
 
+/* The same products as prefill_rows runs them (workgroup-tiled, all rows of the call at once): matrix_kind HX_T_WQKV,
+   HX_T_WO, HX_T_WG or HX_T_WD as above, n_rows a multiple of 256 up to HX_PREFILL_MAX_ROWS, x_dev fp32 [n_rows, in],
+   y_dev fp32 [n_rows, out]; engine, workspace_dev and errors as prefill_rows. */
+int hx_stage_linear_rows(hx_engine *engine, int matrix_kind, int layer, int32_t n_rows, const float *x_dev,
+                         float *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* The LM head on caller-supplied activations followed by the nucleus draw of decode_step_top_p (same kernels, same
    argument meaning; top_p in (0, 1), all outputs but nucleus_sizes_out required): x_dev fp32 [batch, hidden] is
    rounded to bf16 on entry, logits_out fp32 [batch, vocab] receives R(x) W. */

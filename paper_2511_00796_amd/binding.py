@@ -23,7 +23,7 @@ EXPORTS = ["hx_last_error", "hx_weights_bytes", "hx_workspace_bytes", "hx_kv_byt
            "hx_engine_destroy", "hx_weights_pack", "kv_alloc", "kv_free", "prefill_fill", "hx_kv_gather",
            "decode_step", "decode_step_sample", "decode_step_top_p", "prefill_chunk", "prefill_rows", "hx_prefill_workspace_bytes",
            "hx_validate_step_inputs", "hx_set_attn_capture", "hx_stage_schedule", "hx_attention_waves", "hx_plan_product",
-           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_attention_static", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_lm_head_top_p",
+           "hx_stage_rope_append", "hx_stage_attention", "hx_stage_attention_static", "hx_stage_rmsnorm", "hx_stage_linear", "hx_stage_linear_rows", "hx_stage_lm_head_top_p",
            "hx_profile_enable", "hx_profile_sample_every", "hx_profile_read"]
 
 KERNEL_CLASSES = ["attention", "combine", "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm", "norm",
@@ -90,6 +90,7 @@ def load():
         "hx_stage_attention_static": [vp, vp, C.c_int, i32, vp, vp, vp, i32, vp, vp],
         "hx_stage_rmsnorm": [vp, C.c_int, C.c_int, i32, vp, vp, vp],
         "hx_stage_linear": [vp, C.c_int, C.c_int, i32, vp, vp, vp, vp],
+        "hx_stage_linear_rows": [vp, C.c_int, C.c_int, i32, vp, vp, vp, sz, vp],
         "hx_stage_lm_head_top_p": [vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint64, vp, vp, vp, vp, vp],
         "hx_profile_enable": [vp, C.c_uint32],
         "hx_profile_sample_every": [vp, C.c_int32],
@@ -303,6 +304,15 @@ class Engine:
         am = torch.empty(B, dtype=torch.int32, device=self.device) if want_argmax else None
         _check(load().hx_stage_linear(self.handle, kind, layer, B, _ptr(x), _ptr(y), _ptr(am), _stream()))
         return (y, am) if want_argmax else y
+
+    def stage_linear_rows(self, kind: int, layer: int, x: torch.Tensor, workspace: torch.Tensor) -> torch.Tensor:
+        """The product as prefill_rows runs it: x fp32 [rows (multiple of 256), in] -> y fp32 [rows, out]."""
+        s = self.shape
+        n_out = {HX_T_WQKV: s.qkv_dim, HX_T_WO: s.hidden, HX_T_WG: s.intermediate, HX_T_WD: s.hidden}[kind]
+        y = torch.empty(x.shape[0], n_out, dtype=torch.float32, device=self.device)
+        _check(load().hx_stage_linear_rows(self.handle, kind, layer, x.shape[0], _ptr(x), _ptr(y), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()))
+        return y
 
     def stage_lm_head_top_p(self, x: torch.Tensor, positions: torch.Tensor, temperature: float, top_p: float, seed: int,
                             row_ids: Optional[torch.Tensor] = None):

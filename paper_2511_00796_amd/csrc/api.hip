@@ -823,6 +823,57 @@ extern "C" int hx_stage_lm_head_top_p(hx_engine *e, int32_t batch, const float *
     return hx_launch_nucleus(e, batch, logits_out, &sp, tokens_out, logprobs_out, st);
 }
 
+// One product of prefill_rows alone, on caller-supplied rows: x [n_rows, K] fp32 (rounded to bf16 on entry) -> y
+// [n_rows, N] fp32; for HX_T_WG y [n_rows, intermediate] = bf16(SiLU(gate) * up) as fp32.  Same kernels, plan and
+// workspace layout as prefill_rows.
+extern "C" int hx_stage_linear_rows(hx_engine *e, int kind, int layer, int32_t n_rows, const float *x_dev, float *y_dev,
+                                    void *workspace_dev, size_t workspace_bytes, void *stream) {
+    if (!e) return hx_fail(HX_E_NULL, "engine is NULL");
+    if (!x_dev || !y_dev || !workspace_dev) return hx_fail(HX_E_NULL, "a pointer argument is NULL");
+    const hx_model_config *c = &e->cfg;
+    if (c->max_batch != 256) return hx_fail(HX_E_RANGE, "wide products need an engine with max_batch 256, not %d", c->max_batch);
+    if (n_rows < 256 || n_rows > HX_PREFILL_MAX_ROWS || n_rows % 256)
+        return hx_fail(HX_E_RANGE, "n_rows %d is not a multiple of 256 in [256, %d]", n_rows, HX_PREFILL_MAX_ROWS);
+    if (layer < 0 || layer >= c->n_layers) return hx_fail(HX_E_SHAPE, "layer %d out of range", layer);
+    const int R = n_rows / 256;
+    const size_t stride = wide_block_stride(e);
+    if ((uintptr_t)workspace_dev % 256) return hx_fail(HX_E_RANGE, "workspace is not 256-byte aligned");
+    if (workspace_bytes < (size_t)R * stride)
+        return hx_fail(HX_E_RANGE, "workspace holds %zu bytes, %d rows need %zu (hx_prefill_workspace_bytes)", workspace_bytes, n_rows,
+                       (size_t)R * stride);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws0 = (char *)workspace_dev;
+    const hx_layer_map *lm = &e->layers[layer];
+    const hx_ws_map &m = e->map;
+    const hx_matrix *w;
+    size_t in_off;
+    int K, N;
+    switch (kind) {
+        case HX_T_WQKV: w = &lm->wqkv; in_off = m.xp; K = c->hidden; N = e->qkv_dim; break;
+        case HX_T_WO: w = &lm->wo; in_off = m.ap; K = e->q_dim; N = c->hidden; break;
+        case HX_T_WG: w = &lm->wgu; in_off = m.xp; K = c->hidden; N = c->intermediate; break;
+        case HX_T_WD: w = &lm->wd; in_off = m.mp; K = c->intermediate; N = c->hidden; break;
+        default: return hx_fail(HX_E_SHAPE, "tensor kind %d has no wide product", kind);
+    }
+    const bool swiglu = kind == HX_T_WG;
+    const hx_wide_plan plan = hx_plan_wide(w, R, !swiglu);
+    hx_engine view = *e;
+    int rc;
+    for (int b = 0; b < R; ++b) {
+        view.ws = ws0 + (size_t)b * stride;
+        if ((rc = hx_launch_pack_x(&view, 256, x_dev + (size_t)b * 256 * K, K, view.ws + in_off, st))) return rc;
+    }
+    if ((rc = hx_launch_gemm_wide(e, w, R, ws0, stride, in_off, swiglu ? HX_EPI_SWIGLU : HX_EPI_PARTIAL, m.ypart, m.mp, plan, st))) return rc;
+    for (int b = 0; b < R; ++b) {
+        view.ws = ws0 + (size_t)b * stride;
+        float *y = y_dev + (size_t)b * 256 * N;
+        if (swiglu) rc = hx_launch_unpack_x(&view, 256, view.ws + m.mp, N, y, st);
+        else rc = hx_launch_sum_partials(&view, 256, (const float *)(view.ws + m.ypart), plan.splits, (size_t)256 * N, N, y, st);
+        if (rc) return rc;
+    }
+    return HX_OK;
+}
+
 extern "C" int hx_stage_linear(hx_engine *e, int kind, int layer, int32_t batch, const float *x_dev, float *y_dev,
                                int32_t *argmax_out_dev, void *stream) {
     int rc = check_step_args(e, nullptr, batch, 1);

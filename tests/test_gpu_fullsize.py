@@ -141,6 +141,53 @@ def test_linear_stages_at_the_benchmark_shapes(hx, model, batch):
     release(eng)
 
 
+@pytest.mark.parametrize("model", ["qwen2-7b", "qwen2-14b"])
+def test_prompt_row_products_at_the_benchmark_shapes(hx, model):
+    """The workgroup-tiled products of prefill_rows at the 7B and 14B layer shapes over 1 024 rows (K up to 18 944 in two
+    K-splits, 256- and 192-column tiles, a partly filled last round of workgroups): first and last row of every block of
+    256 and seeded further rows against the oracle's ascending-k sum, to fp32 reassociation; SiLU * mul to one bf16
+    step on at most 1 % of the values."""
+    base = synth.QWEN_7B if model == "qwen2-7b" else synth.QWEN_14B
+    eng, shape, hw = one_layer_engine(hx, base, 256)
+    n_rows = 1024
+    ws = torch.empty(hx.prefill_workspace_bytes(eng.cfg, n_rows), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(7)
+    rows = sorted({r for b in range(0, n_rows, 256) for r in (b, b + 255)} | {int(r) for r in rng.integers(0, n_rows, 8)})
+    pool = ThreadPoolExecutor(max_workers=16)
+    worst = {}
+    for kind, name, K in ((hx.HX_T_WQKV, "wqkv", shape.hidden), (hx.HX_T_WO, "wo", shape.q_dim), (hx.HX_T_WD, "wd", shape.intermediate)):
+        x = rng.normal(0, 1, size=(n_rows, K)).astype(np.float32)
+        xr = bits_to_f32(synth.as_u16(torch.from_numpy(x).to(torch.bfloat16)))
+        y = eng.stage_linear_rows(kind, 0, dev(x), ws).cpu().numpy()
+        wabs = np.abs(bits_to_f32(hw[name])).astype(np.float32)
+        for b, ref in pool.map(lambda b: (b, oracle.linear(xr[b], hw[name])), rows):
+            mag = np.abs(xr[b]) @ wabs
+            rel = np.abs(y[b] - ref) / (mag + 1e-30)
+            worst[name] = max(worst.get(name, 0.0), float(rel.max()))
+            assert np.all(np.abs(y[b] - ref) <= 1e-5 * mag + 1e-7), (name, b, float(rel.max()))
+    x = rng.normal(0, 1, size=(n_rows, shape.hidden)).astype(np.float32)
+    xr = bits_to_f32(synth.as_u16(torch.from_numpy(x).to(torch.bfloat16)))
+    y = eng.stage_linear_rows(hx.HX_T_WG, 0, dev(x), ws).cpu().numpy()
+    wabs_gu = np.abs(bits_to_f32(hw["wg"])) + np.abs(bits_to_f32(hw["wu"]))
+
+    def swiglu(b):
+        gt = oracle.linear(xr[b], hw["wg"])
+        up = oracle.linear(xr[b], hw["wu"])
+        sg = np.array([oracle.silu(float(a)) for a in gt], dtype=np.float32)
+        return b, bits_to_f32(oracle.bf16_round_bits(sg * up))
+    flips = total = 0
+    for b, ref in pool.map(swiglu, rows):
+        slack = GATE_UP_SLACK * (np.abs(xr[b]) @ wabs_gu)
+        assert np.all(np.abs(y[b] - ref) <= np.abs(ref) * 2.0 ** -7 + slack), ("gate|up", b)
+        flips += int((y[b] != ref).sum())
+        total += ref.size
+    assert flips <= 0.01 * total, (flips, total)
+    pool.shutdown()
+    print("%s, %d rows through the prompt-row products: worst |err| / sum|x w|: %s; gate|up: %d of %d values one bf16 step off"
+          % (model, n_rows, {k: "%.1e" % v for k, v in worst.items()}, flips, total))
+    release(eng, ws)
+
+
 @pytest.mark.parametrize("name", ["7b-b128", "14b-b64"])
 def test_attention_stage_at_the_benchmark_length_draws(hx, name):
     """The attention kernel alone on the length draws of the 7B/b128 and 14B/b64 workloads (runs of ~128 tiles that
