@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--prefill-rows-per-call", type=int, default=256, metavar="M",
                     help="with --prefill: rows per call; above 256 (a multiple of 256 that divides P) the calls go through "
                          "prefill_rows, whose products run over all rows of the call at once")
+    ap.add_argument("--prefill-prompts", type=int, default=32, metavar="Q",
+                    help="with --prefill-rows-per-call above 256: prompts per pass (32; fewer for counter runs)")
     ap.add_argument("--prefill-rows-per-seq", type=int, default=256, metavar="N",
                     help="with --prefill: consecutive positions of one prompt per call (256 = one prompt per call, "
                          "2 = all 128 prompts in every call)")
@@ -225,7 +227,7 @@ def main():
                 st_i = torch.cuda.current_stream() if i == 0 else torch.cuda.Stream()
                 wide_lanes.append((kv_i, st_i, torch.empty(binding.prefill_workspace_bytes(eng.cfg, M), dtype=torch.uint8, device="cuda")))
             wide_ws = wide_lanes[0][2]
-            n_seq = min(B, 32)                                    # 32 prompts are enough for a steady figure
+            n_seq = min(B, args.prefill_prompts)                  # 32 prompts are enough for a steady figure
             assert n_seq % n_streams == 0
             rows_of_seq = [table_d[g:g + 1].expand(M, -1).contiguous() for g in range(n_seq)]
             calls = n_seq * (P // M)
