@@ -60,6 +60,18 @@ int main() {
             EXPECT(decode_step_top_p(e, kv, 1, ip, ip, ip, ip, 4, 1.0f, 1.5f, 1, nullptr, fp, op, fp, nullptr, nullptr) == HX_E_RANGE);
             EXPECT(decode_step_top_p(e, kv, 1, ip, ip, ip, ip, 4, 1.0f, 0.5f, 1, nullptr, nullptr, op, fp, nullptr, nullptr) == HX_E_NULL);
             EXPECT(prefill_chunk(e, kv, c.max_batch + 1, ip, ip, ip, ip, 4, nullptr) == HX_E_RANGE);
+            // prompt rows: refused before anything is launched (row count, engine size, workspace)
+            EXPECT(prefill_rows(e, kv, 300, ip, ip, ip, ip, 4, fake, (size_t)1 << 40, nullptr) == HX_E_RANGE);
+            EXPECT(prefill_rows(e, kv, 256, ip, ip, ip, ip, 4, nullptr, 0, nullptr) == HX_E_NULL);
+            EXPECT(prefill_rows(e, nullptr, 256, ip, ip, ip, ip, 4, fake, (size_t)1 << 40, nullptr) == HX_E_NULL);
+            if (c.max_batch == 256) {
+                EXPECT(prefill_rows(e, kv, 256, ip, ip, ip, ip, 4, fake, 1024, nullptr) == HX_E_RANGE);
+                EXPECT(hx_stage_linear_rows(e, HX_T_WLM, 0, 256, fp, fp, fake, (size_t)1 << 40, nullptr) == HX_E_SHAPE);
+                EXPECT(hx_stage_linear_rows(e, HX_T_WO, 0, 256, fp, fp, fake, 1024, nullptr) == HX_E_RANGE);
+            } else {
+                EXPECT(prefill_rows(e, kv, 256, ip, ip, ip, ip, 4, fake, (size_t)1 << 40, nullptr) == HX_E_RANGE);
+                EXPECT(hx_stage_linear_rows(e, HX_T_WO, 0, 256, fp, fp, fake, (size_t)1 << 40, nullptr) == HX_E_RANGE);
+            }
             EXPECT(prefill_fill(kv, c.n_layers, fake, fake, ip, ip, 4, 1, 16, nullptr) == HX_E_SHAPE);
             EXPECT(prefill_fill(kv, 0, fake, fake, ip, ip, 4, 0, 16, nullptr) == HX_E_RANGE);
             EXPECT(hx_kv_gather(kv, 0, fake, nullptr, ip, ip, 4, 1, 16, nullptr) == HX_E_NULL);
