@@ -137,6 +137,39 @@ def test_prompts_through_one_wide_call_match_dense_causal_recomputation(hx, name
     print("%s: %d rows in one prefill_rows call: worst logit err / max|logit| %.3e" % (name, wide, worst))
 
 
+def test_the_most_rows_a_call_takes(hx):
+    """HX_PREFILL_MAX_ROWS = 8 192 rows (32 blocks) of one prompt in one call, then one decode step: the logits against the
+    oracle's dense causal recomputation of the 8 193-token prompt."""
+    s = SHAPES["d64_g2"]
+    seed = 321
+    ow, g, layers = host_model(s, seed)
+    cfg = oracle.make_config(s)
+    rng = np.random.default_rng(seed)
+    ctx = np.array([8193], dtype=np.int32)
+    prompts = [rng.integers(0, s.vocab, size=int(n)).astype(np.int32) for n in ctx]
+    table, nb = synth.block_table(ctx + 1, s.block_size, seed)
+    rows = prompt_rows(ctx)
+    assert len(rows) == 8192
+    eng = build(hx, s, seed, int(ctx.max()) + 1)
+    kv = hx.KVCache(eng, nb)
+    kv.pool.fill_(0xFF)
+    feed(hx, eng, kv, prompts, table, rows, 8192)
+    pos = (ctx - 1).astype(np.int32)
+    last = np.array([prompts[0][-1]], dtype=np.int32)
+    logits = torch.empty(1, s.vocab, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+    eng.decode_step(kv, dev(last), dev(pos), dev(pos + 1), dev(table), logits, nxt)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    ref = oracle.full_causal(cfg, ow, prompts[0])[0][-1]
+    scale = float(np.abs(ref).max())
+    err = float(np.abs(gl[0] - ref).max())
+    print("8192 rows in one call: logit err / max|logit| %.3e" % (err / scale))
+    assert err <= LOGIT_TOL * scale, (err, scale)
+    with pytest.raises(hx.HexError):
+        hx.prefill_workspace_bytes(eng.cfg, 8192 + 256)
+
+
 def test_two_calls_on_two_streams_share_one_engine(hx):
     """prefill_rows keeps its state in the workspace it is given: two calls on two streams, each with its own workspace
     and cache, through ONE engine leave exactly the caches the same calls leave when run one after the other."""
