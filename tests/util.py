@@ -1,6 +1,8 @@
 """Helpers shared by the tests: host copies of synthetic models in the oracle's structs."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 import oracle
@@ -88,6 +90,8 @@ class OracleRows:
                 self.layer_bias[layer] = self.layer_w["bqkv"].copy()
             for r, att in self.pool.map(run, self.rows):
                 self.attn[r].append(att)
+            if os.environ.get("HX_PARITY_PROGRESS"):     # long every-row runs: one line per layer of oracle work
+                print("oracle%s: layer %d of %d rows done" % (" (reordered)" if self.descending else "", layer, len(self.rows)), flush=True)
             if layer in self.keep_layers:
                 self.x_after[layer] = {r: self.x[r].copy() for r in self.rows}
                 # sum_k |x_k| |w_kn| of every product of the layer, per kept row: the scale of its fp32 rounding error
