@@ -168,7 +168,10 @@ int hx_kv_gather(hx_kv *kv, int layer, void *k_out_dev, void *v_out_dev,
      logits_out  fp32 [batch, vocab] or NULL (then the logits are not written)
      next_tokens_out int32 [batch]   smallest index attaining the row maximum of the logits
    Side effect: K and V of the new token are written into `kv` at `positions` for every layer.
-   The step is deterministic: the same inputs give the same bits. */
+   The step is deterministic: the same inputs give the same bits.  It allocates nothing, uses no memset and does not
+   synchronise the host, so a caller may capture it into a HIP graph -- after one ordinary call with the same batch
+   size class, because the first launch of each kernel variant sets its attributes (the same holds for prefill_chunk,
+   prefill_rows and the sampling steps). */
 int decode_step(hx_engine *engine, hx_kv *kv, int32_t batch, const int32_t *tokens,
                 const int32_t *positions, const int32_t *seq_lens, const int32_t *block_table,
                 int32_t max_blocks_per_seq, float *logits_out, int32_t *next_tokens_out, void *stream);
