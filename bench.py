@@ -92,6 +92,9 @@ def main():
                     help="override the workload's batch (same model shape and length law; reported as <workload>@bB): how "
                          "the kernels behave at other row counts, e.g. 4 rows = one m-group")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed steps with every kernel class bracketed by events")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of ONE HIP graph holding a whole step instead of eager launches (reported as such; the "
+                         "dominant kernel is then timed in a separate eager pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16,
                     help="sequences the CPU baseline recomputes (default 16: one per host core of the GPU box, ~20 s of CPU work "
@@ -374,12 +377,34 @@ def main():
     torch.cuda.synchronize()
     # HIP events around the dominant kernel only, and around every 4th of its launches (layers 0, 4, 8, ...: the same
     # K/V lengths in every layer): a pair of events costs the stream ~5 us, 0.15 ms per step if all 28 were bracketed
-    eng.profile_enable(["attention"], every=4)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        # one graph = one step; no events inside the capture, so the attention kernel is timed in an eager pass after
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                one_step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        eng.profile_enable(["attention"], every=4)
+        for _ in range(args.steps):
+            one_step()
+        torch.cuda.synchronize()
+    else:
+        eng.profile_enable(["attention"], every=4)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     attn_ms, attn_n = eng.profile_read("attention")
     eng.profile_enable([])
 
@@ -404,7 +429,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": s.name, "batch": wl.batch, "kv_lengths": "%s[%d,%d]" % (wl.length_law, wl.lo, wl.hi),
-                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves(),
+                   "total_kv_tokens": int(dw.seq_lens.sum()), "block_size": s.block_size, "attention_waves": eng.attention_waves(), "launch": "hip graph replay" if args.graph else "eager",
                    "kv_cache": "fp8-e4m3" if fp8 else "bf16",
                    "token_choice": ("sample T=%g%s + logprob" % (args.sample, " top-p %g" % args.top_p if args.top_p < 1 else ""))
                    if args.sample > 0 else "greedy"},
