@@ -172,6 +172,26 @@ def test_sequences_leave_and_join_between_steps(hx):
             assert float((logits[i] - ref).abs().max()) <= 1e-3 * scale, (b, float((logits[i] - ref).abs().max()), scale)
             assert int(nxt[i]) == int(alone[b][1][0])
 
+    # What an RL consumer keeps of a step is the token drawn and its log-probability under the behaviour policy: the
+    # same sequence sampled alone and inside a batch (same seed, same row id) draws the same token, and the
+    # log-probabilities differ by no more than the logits do.
+    def sample(rows):
+        rows = list(rows)
+        B = len(rows)
+        ctx = ctx_all[rows]
+        tok = torch.empty(B, dtype=torch.int32, device="cuda")
+        lp = torch.empty(B, dtype=torch.float32, device="cuda")
+        eng.decode_step_sample(kv, dev(tokens_all[rows].astype(np.int32)), dev(ctx), dev(ctx + 1), dev(table_all[rows]), 0.8, 2024,
+                               None, tok, lp, row_ids=dev(np.array(rows, dtype=np.int32)))
+        torch.cuda.synchronize()
+        return tok.cpu().numpy(), lp.cpu().numpy()
+
+    together_tok, together_lp = sample(range(6))
+    for i, b in enumerate(range(6)):
+        tok, lp = sample([b])
+        assert int(tok[0]) == int(together_tok[i]), b
+        assert abs(float(lp[0]) - float(together_lp[i])) <= 2e-3, (b, float(lp[0]), float(together_lp[i]))
+
 
 def test_new_policy_version_packed_into_a_live_engine(hx):
     """hx_weights_pack overwrites the streaming-layout weights in place: after packing version B the engine is
