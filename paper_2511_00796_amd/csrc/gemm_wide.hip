@@ -1,7 +1,7 @@
 // Products for many prompt rows at once: C[R x 256 rows][N] = X W with BOTH operands tiled through LDS, so that a
 // weight is read from HBM once per call instead of once per 256 rows (prompt processing, Section 1 stage (i) of the
 // rollout; the step before decoding).  The streaming kernel of gemm.hip keeps one weight tile per wavefront in
-// registers and is right for up to 256 rows; here a workgroup owns a 256 x 256 tile of the output.
+// registers and is right for up to 256 rows; here a workgroup owns a 256 x 256 (or 256 x 192) tile of the output.
 //
 // Layouts are the decode step's (hx_internal.h): weights [n_tile][k_step][lane][8], activations of each 256-row block
 // [k_step][8 m-groups][lane][8] in that block's workspace.  Both are already in matrix-core operand order, so
@@ -13,10 +13,11 @@
 // global -> registers -> LDS: requested three chunks ahead (two register sets), written to LDS one chunk ahead, two
 // LDS stages, one barrier per chunk.  The barrier of chunk c + 1 is passed BEFORE the last k-step of chunk c is
 // multiplied, so that the first operand reads of the next chunk hide behind those products.  Measured on MI355X
-// (7B gate|up, 2048 rows): 39 % of the bf16 matrix peak; the kernel with the copies alone takes as long as the whole
-// kernel -- what bounds it is the rate at which the compute units can draw from the L2 (about 8.6 TB/s over the chip,
-// 34 GB/s per compute unit when all are busy, however local the traffic), not the matrix cores (66 % with the copies
-// removed) and not the LDS.  The direct global -> LDS path (global_load_lds) was slower (37 %).
+// (7B gate|up, 2048 rows): 45-48 % of the bf16 matrix peak.  The kernel with its copies alone (no arithmetic) takes as
+// long as the whole kernel: what bounds it is the rate at which the compute units can draw from the L2 (8-9 TB/s over
+// the chip, about 35 GB/s per compute unit when all are busy, however local the traffic: 80 % of the L2 requests of
+// this product hit), not the matrix cores (66 % with the copies removed) and not the LDS.  The direct global -> LDS
+// path (global_load_lds) was slower; a larger output tile, the only way to draw fewer bytes per flop, spills.
 //
 // Workgroup numbering: consecutive workgroup ids go to different XCDs, so id -> (xcd, slot); the workgroups of one
 // XCD take all row blocks of a few column blocks and walk K in step: each XCD's L2 sees every weight once.
